@@ -1,0 +1,142 @@
+/* d3.h -- C ABI of the MI355X (gfx950) implementation of Position-Aware Depth
+ * Decay Decoding (D^3): the autoregressive decode step of a Llama-style decoder
+ * that runs only floor(L * alpha^i) of its L blocks when generating token T_i.
+ *
+ * Conventions
+ *   - Every function returns D3_OK (0) or a negative d3_status.  Nothing throws
+ *     or aborts.  d3_last_error() gives the message of the calling thread's last
+ *     failure (library-owned, valid until that thread's next failing call).
+ *   - "dev" pointers are HIP device pointers, "host" pointers are ordinary
+ *     memory.  The library allocates NO device memory: weights, KV cache,
+ *     workspace, token and logit buffers are caller-owned and must outlive the
+ *     context.  Device work is enqueued on the HIP stream the caller passes
+ *     (a hipStream_t cast to void*; NULL = the null stream) and is asynchronous;
+ *     argument checks are synchronous.
+ *   - Token time step i (Section 1, Section 3.4): T_0 is the token produced by
+ *     the prompt pass, which runs all L blocks (Section 3.2); decode step i >= 1
+ *     consumes T_{i-1}, writes cache row n_ctx = P + i - 1 and produces T_i with
+ *     keep[i] = floor(L * alpha^i) blocks.  All sequences of a batch share i and
+ *     therefore the executed blocks (Section 1, challenge (ii); Table 1).
+ *   - Layouts: linear weights row-major [out][in], float32 or bf16; RMSNorm
+ *     gains float32; KV cache [L][max_batch][H_kv][max_seq][head_dim] for K and
+ *     for V (keys stored after the rotary embedding), float32 or bf16.
+ */
+#ifndef D3_H
+#define D3_H
+#include <stddef.h>
+#include <stdint.h>
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    D3_OK = 0,
+    D3_EINVAL = -1,  /* bad scalar argument or NULL pointer */
+    D3_ESHAPE = -2,  /* model shape or batch outside what the kernels support */
+    D3_ERANGE = -3,  /* position or step outside the cache / the plan */
+    D3_ESTATE = -4,  /* call out of order (no plan, no prefill, wrong step) */
+    D3_EDEVICE = -5  /* a HIP call failed */
+} d3_status;
+
+typedef enum { D3_F32 = 0, D3_BF16 = 1 } d3_dtype;
+typedef enum { D3_FILL_COPY = 0 } d3_fill_mode;
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rms_eps, rope_base;
+    int32_t weight_dtype; /* d3_dtype of every linear weight and the embedding table */
+    int32_t kv_dtype;     /* d3_dtype of the KV cache */
+    int32_t max_batch, max_seq;
+} d3_model_desc;
+
+/* One decoder block (Llama-2 blocks, Section 4.1): dev pointers.
+ * attn_norm/mlp_norm: float32 [d_model].  wq [n_heads*head_dim][d_model];
+ * wk, wv [n_kv_heads*head_dim][d_model]; wo [d_model][n_heads*head_dim];
+ * w_gate, w_up [d_ffn][d_model]; w_down [d_model][d_ffn]. */
+typedef struct {
+    const void *attn_norm, *wq, *wk, *wv, *wo, *mlp_norm, *w_gate, *w_up, *w_down;
+} d3_layer_weights;
+
+/* tok_emb, lm_head: dev [vocab][d_model] (weight_dtype); final_norm: dev float32 [d_model];
+ * layers: HOST array of n_layers entries (copied by d3_create). */
+typedef struct {
+    const void *tok_emb;
+    const d3_layer_weights *layers;
+    const void *final_norm, *lm_head;
+} d3_weights;
+
+typedef struct d3_ctx d3_ctx;
+
+const char *d3_last_error(void);
+
+/* Depth schedule and layer-index table (Section 3.4: power-law decay
+ * floor(L * alpha^i); Table 6: drop-layer set starting at `start`).  Pure host
+ * code, needs no GPU.  For i in [0, n_steps):
+ *   pow_0 = 1, pow_i = pow_{i-1} * alpha (binary64);
+ *   keep[i] = max(min_keep, floor(L * pow_i));  n_i = L - keep[i];
+ *   drop_begin[i] = min(start_layer, L - n_i);  dropped = [drop_begin[i], drop_begin[i] + n_i);
+ *   layer_ids[i*L + j] = j-th executed block in increasing order, -1 for j >= keep[i].
+ * Host arrays of n_steps (keep, drop_begin) and n_steps*L (layer_ids) int32,
+ * caller-owned; any may be NULL.  D3_EINVAL unless L >= 1, 0 < alpha <= 1,
+ * 0 <= start_layer < L, 0 <= min_keep <= L, n_steps >= 0. */
+int d3_plan_depth(int32_t L, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps,
+                  int32_t *keep, int32_t *drop_begin, int32_t *layer_ids);
+
+/* Bytes of device workspace d3_create needs for this model (0 on a bad desc). */
+size_t d3_workspace_size(const d3_model_desc *desc);
+
+/* Build a context around caller-owned device buffers.  k_cache / v_cache: dev,
+ * [L][max_batch][H_kv][max_seq][head_dim] of kv_dtype.  workspace: dev, at least
+ * d3_workspace_size() bytes, 256-byte aligned; the library keeps the residual
+ * stream, activations, attention partials and the layer-index table there.
+ * D3_ESHAPE unless head_dim in {64,128}, n_heads % n_kv_heads == 0,
+ * d_model % 8 == 0, d_ffn % 8 == 0, 1 <= max_batch <= 32. */
+int d3_create(d3_ctx **out, const d3_model_desc *desc, const d3_weights *weights, void *k_cache,
+              void *v_cache, void *workspace, size_t workspace_bytes);
+int d3_destroy(d3_ctx *ctx);
+
+/* Start a request's schedule: computes the plan with d3_plan_depth and uploads
+ * the layer-index table (n_steps <= 4096).  The next d3_decode_step must be
+ * step 1.  Keeps the cache contents and row count. */
+int d3_set_plan(d3_ctx *ctx, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps);
+
+/* Prompt pass (Section 3.1 "initiation phase"; all L blocks, Section 3.2).
+ * tokens: dev int32 [B][P].  Writes cache rows [pos_begin, pos_begin + P) of
+ * every block for sequences 0..B-1, causal attention over rows [0, pos_begin+p].
+ * pos_begin must be 0 (fresh request) or the current row count (continue on the
+ * same cache, e.g. after d3_fill_missing_kv).  next_tok: dev int32 [B] = T_0
+ * (argmax of the last position's logits, lowest index on ties); logits: dev
+ * float32 [B][vocab] or NULL; hidden_dump: dev float32 [L+1][B][d_model] or
+ * NULL (residual stream of the last prompt position after the embedding and
+ * after each block).  Resets the step counter: the next decode step is 1. */
+int d3_prefill(d3_ctx *ctx, const int32_t *tokens, int32_t B, int32_t P, int32_t pos_begin,
+               int32_t *next_tok, float *logits, float *hidden_dump, void *hip_stream);
+
+/* One decode step (Section 3.1 "generation phase"; Section 3.4).  tok_in: dev
+ * int32 [B] = T_{step_i - 1}; runs the keep[step_i] executed blocks of the plan,
+ * appends one cache row per sequence in each of them, and writes tok_out: dev
+ * int32 [B] = T_{step_i}; logits: dev float32 [B][vocab] or NULL; hidden_dump:
+ * dev float32 [keep+1][B][d_model] or NULL.  Skipped blocks leave the hidden
+ * state unchanged and their cache rows unwritten (see d3_fill_missing_kv).
+ * D3_ESTATE unless step_i == previous step + 1; D3_ERANGE if step_i is outside
+ * the plan or the cache is full. */
+int d3_decode_step(d3_ctx *ctx, const int32_t *tok_in, int32_t step_i, int32_t *tok_out,
+                   float *logits, float *hidden_dump, void *hip_stream);
+
+/* Missing-state fill (Section 1, challenge (i); Section 3.2): for every cache
+ * row p in [pos_begin, pos_end) that a decode step wrote with a reduced depth,
+ * and every block l that step dropped, K[l][.][p], V[l][.][p] <- K[src][.][p],
+ * V[src][.][p], where src is the last executed block before the drop window
+ * (the first one after it when the window starts at block 0; zeros when no
+ * block ran).  mode must be D3_FILL_COPY.  Rows written by the prompt pass need
+ * nothing.  May be called every step with a one-row range or once before the
+ * cache is reused; the result is the same. */
+int d3_fill_missing_kv(d3_ctx *ctx, int32_t pos_begin, int32_t pos_end, int32_t mode, void *hip_stream);
+
+/* Current number of cache rows per sequence. */
+int32_t d3_n_ctx(const d3_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

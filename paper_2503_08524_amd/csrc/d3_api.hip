@@ -1,0 +1,408 @@
+// C ABI of the D^3 decode path: context, argument checks, and the per-step orchestration
+// that launches only the blocks the schedule keeps (Section 3.4).  All device memory is the
+// caller's; this file owns host state only.
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/d3.h"
+#include "d3_common.h"
+#include "d3_error.h"
+
+using namespace d3;
+
+namespace {
+
+constexpr int kMaxPlanSteps = 4096;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {          // byte offsets into the workspace
+    size_t x, qkv, attn_o, act, part_o, part_ml, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, layer_table, total;
+};
+
+// The vector-ALU GEMV stages one column of its input in LDS.
+bool alu_fits(const d3_model_desc& d) {
+    const int widest = d.d_model > d.d_ffn ? d.d_model : d.d_ffn;
+    return gemv_alu_max_cols(widest, d.weight_dtype) >= 1 && gemv_alu_max_cols(d.n_heads * d.head_dim, d.weight_dtype) >= 1;
+}
+// The matrix-core path takes bf16 weights, K in steps of 32 and rows in tiles of 16.
+bool mfma_fits(const d3_model_desc& d) {
+    const int qdim = d.n_heads * d.head_dim;
+    return d.weight_dtype == D3_BF16 && d.d_model % 32 == 0 && d.d_ffn % 32 == 0 && qdim % 32 == 0 && d.vocab % 16 == 0;
+}
+
+int check_desc(const d3_model_desc* d) {
+    if (!d) return fail(D3_EINVAL, "model desc is NULL");
+    if (d->n_layers < 1 || d->d_model < 1 || d->n_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 1 || d->vocab < 2)
+        return fail(D3_ESHAPE, "model dimensions must be positive");
+    if (d->head_dim != 64 && d->head_dim != 128) return fail(D3_ESHAPE, "head_dim must be 64 or 128 (got %d)", d->head_dim);
+    if (d->n_heads % d->n_kv_heads != 0)
+        return fail(D3_ESHAPE, "n_heads (%d) must be a multiple of n_kv_heads (%d)", d->n_heads, d->n_kv_heads);
+    if (d->d_model % 8 != 0 || d->d_ffn % 8 != 0) return fail(D3_ESHAPE, "d_model and d_ffn must be multiples of 8");
+    if (d->vocab % 2 != 0) return fail(D3_ESHAPE, "vocab must be even (got %d)", d->vocab);
+    if (d->max_batch < 1 || d->max_batch > kMaxCols) return fail(D3_ESHAPE, "max_batch must be in [1, %d] (got %d)", kMaxCols, d->max_batch);
+    if (d->max_seq < 1 || d->max_seq > kMaxSplits * 8192) return fail(D3_ESHAPE, "max_seq must be in [1, %d]", kMaxSplits * 8192);
+    if ((d->weight_dtype != D3_F32 && d->weight_dtype != D3_BF16) || (d->kv_dtype != D3_F32 && d->kv_dtype != D3_BF16))
+        return fail(D3_EINVAL, "weight_dtype and kv_dtype must be D3_F32 or D3_BF16");
+    if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(D3_EINVAL, "rms_eps must be >= 0 and rope_base > 1");
+    if (!alu_fits(*d) && !mfma_fits(*d))
+        return fail(D3_ESHAPE, "d_model / d_ffn fit neither the LDS-staged GEMV nor the matrix-core path");
+    return D3_OK;
+}
+
+Layout make_layout(const d3_model_desc& d) {
+    const size_t C = kMaxCols, qdim = (size_t)d.n_heads * d.head_dim;
+    const size_t qkv_dim = (size_t)(d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+    const size_t s_dim = qdim > (size_t)d.d_model ? qdim : (size_t)d.d_model;
+    Layout l{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += align_up(bytes); return at; };
+    l.x = take(C * d.d_model * 4);
+    l.qkv = take(C * qkv_dim * 4);
+    l.attn_o = take(C * qdim * 4);
+    l.act = take(C * (size_t)d.d_ffn * 4);
+    l.part_o = take(C * d.n_heads * kMaxSplits * (size_t)d.head_dim * 4);
+    l.part_ml = take(C * d.n_heads * kMaxSplits * 2 * 4);
+    l.logits = take(C * (size_t)d.vocab * 4);
+    l.s_hi = take(C * s_dim * 2);
+    l.s_lo = take(C * s_dim * 2);
+    l.f_hi = take(C * (size_t)d.d_ffn * 2);
+    l.f_lo = take(C * (size_t)d.d_ffn * 2);
+    l.inv_freq = take((size_t)d.head_dim / 2 * 8);
+    l.layer_table = take((size_t)kMaxPlanSteps * d.n_layers * 4);
+    l.total = o;
+    return l;
+}
+
+}  // namespace
+
+struct d3_ctx {
+    d3_model_desc desc;
+    std::vector<d3_layer_weights> layers;
+    const void *tok_emb, *final_norm, *lm_head;
+    char *k_cache, *v_cache, *ws;
+    Layout lay;
+    int n_cu;
+    bool mfma_ok, alu_ok;         // which projection paths the shapes fit
+    // plan
+    bool has_plan;
+    int n_steps;
+    std::vector<int32_t> keep, drop_begin, layer_ids;
+    // request state
+    bool prefilled;
+    int B, n_ctx, last_step;
+    std::vector<int32_t> row_drop_begin, row_n_drop;   // per cache row: what the step that wrote it dropped
+
+    template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
+    size_t kv_layer_bytes() const {
+        return (size_t)desc.max_batch * desc.n_kv_heads * desc.max_seq * desc.head_dim * (desc.kv_dtype == D3_F32 ? 4 : 2);
+    }
+};
+
+#define D3_HIP(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (hipError_t)(expr);                                                       \
+        if (e_ != hipSuccess) return fail(D3_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+extern "C" const char* d3_last_error(void) { return error_buffer(); }
+
+extern "C" size_t d3_workspace_size(const d3_model_desc* desc) {
+    if (check_desc(desc) != D3_OK) return 0;
+    return make_layout(*desc).total;
+}
+
+extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weights* w, void* k_cache, void* v_cache,
+                         void* workspace, size_t workspace_bytes) {
+    if (!out) return fail(D3_EINVAL, "d3_create: out is NULL");
+    *out = nullptr;
+    int rc = check_desc(desc);
+    if (rc != D3_OK) return rc;
+    if (!w || !w->tok_emb || !w->layers || !w->final_norm || !w->lm_head) return fail(D3_EINVAL, "d3_create: weights has a NULL field");
+    for (int l = 0; l < desc->n_layers; ++l) {
+        const d3_layer_weights& lw = w->layers[l];
+        if (!lw.attn_norm || !lw.wq || !lw.wk || !lw.wv || !lw.wo || !lw.mlp_norm || !lw.w_gate || !lw.w_up || !lw.w_down)
+            return fail(D3_EINVAL, "d3_create: block %d has a NULL weight pointer", l);
+    }
+    if (!k_cache || !v_cache || !workspace) return fail(D3_EINVAL, "d3_create: cache or workspace is NULL");
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0) return fail(D3_EINVAL, "d3_create: workspace must be %zu-byte aligned", kAlign);
+    const Layout lay = make_layout(*desc);
+    if (workspace_bytes < lay.total) return fail(D3_EINVAL, "d3_create: workspace has %zu bytes, %zu needed", workspace_bytes, lay.total);
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    D3_HIP(hipGetDevice(&dev));
+    D3_HIP(hipGetDeviceProperties(&prop, dev));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(D3_EDEVICE, "d3_create: built for gfx950, device is %s", prop.gcnArchName);
+
+    d3_ctx* c = new (std::nothrow) d3_ctx();
+    if (!c) return fail(D3_EINVAL, "d3_create: out of host memory");
+    c->desc = *desc;
+    c->layers.assign(w->layers, w->layers + desc->n_layers);
+    c->tok_emb = w->tok_emb; c->final_norm = w->final_norm; c->lm_head = w->lm_head;
+    c->k_cache = static_cast<char*>(k_cache); c->v_cache = static_cast<char*>(v_cache); c->ws = static_cast<char*>(workspace);
+    c->lay = lay;
+    c->n_cu = prop.multiProcessorCount;
+    c->mfma_ok = mfma_fits(*desc);
+    c->alu_ok = alu_fits(*desc);
+    c->has_plan = false; c->n_steps = 0;
+    c->prefilled = false; c->B = 0; c->n_ctx = 0; c->last_step = 0;
+    c->row_drop_begin.assign(desc->max_seq, 0);
+    c->row_n_drop.assign(desc->max_seq, 0);
+
+    // rotary frequencies base^(-2j/hd), in binary64
+    std::vector<double> inv(desc->head_dim / 2);
+    for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
+    hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy failed: %s", hipGetErrorString(e)); }
+    *out = c;
+    return D3_OK;
+}
+
+extern "C" int d3_destroy(d3_ctx* ctx) {
+    delete ctx;
+    return D3_OK;
+}
+
+extern "C" int32_t d3_n_ctx(const d3_ctx* ctx) { return ctx ? ctx->n_ctx : 0; }
+
+extern "C" int d3_set_plan(d3_ctx* ctx, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps) {
+    if (!ctx) return fail(D3_EINVAL, "d3_set_plan: ctx is NULL");
+    if (n_steps < 1 || n_steps > kMaxPlanSteps) return fail(D3_EINVAL, "d3_set_plan: n_steps must be in [1, %d] (got %d)", kMaxPlanSteps, n_steps);
+    const int L = ctx->desc.n_layers;
+    std::vector<int32_t> keep(n_steps), drop(n_steps), ids((size_t)n_steps * L);
+    int rc = d3_plan_depth(L, alpha, start_layer, min_keep, n_steps, keep.data(), drop.data(), ids.data());
+    if (rc != D3_OK) return rc;
+    D3_HIP(hipMemcpy(ctx->at<int32_t>(ctx->lay.layer_table), ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    ctx->keep.swap(keep); ctx->drop_begin.swap(drop); ctx->layer_ids.swap(ids);
+    ctx->n_steps = n_steps;
+    ctx->has_plan = true;
+    ctx->last_step = 0;
+    return D3_OK;
+}
+
+namespace {
+
+struct HeadOut {       // what to do after the last block
+    int first_col, n_cols;      // columns that get logits
+    float* logits;              // dev [n_cols][V]
+    int32_t* tok_out;           // dev [n_cols]
+};
+
+// Attention split geometry for a pass whose longest context is `ctx` rows.
+void pick_splits(const d3_ctx* c, int ncols, int ctx, int* split_len, int* n_splits) {
+    const int heads = ncols * c->desc.n_heads;
+    int want = (2 * c->n_cu + heads - 1) / heads;
+    if (want < 1) want = 1;
+    if (want > kMaxSplits) want = kMaxSplits;
+    int len = ((ctx + want - 1) / want + 63) / 64 * 64;
+    if (len < 64) len = 64;
+    int n = (ctx + len - 1) / len;
+    if (n > kMaxSplits) { len = ((ctx + kMaxSplits - 1) / kMaxSplits + 63) / 64 * 64; n = (ctx + len - 1) / len; }
+    *split_len = len;
+    *n_splits = n;
+}
+
+// One pass of `ncols` columns through the listed blocks.  hidden_dump (or NULL): dev
+// [(n_ids+1)][dump_cols][d], fed from columns [dump_first, dump_first + dump_cols).
+int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_t* ids, int n_ids,
+            float* hidden_dump, int dump_first, int dump_cols, const HeadOut* head, hipStream_t s) {
+    const d3_model_desc& d = c->desc;
+    const int dm = d.d_model, hd = d.head_dim, qdim = d.n_heads * hd, kvdim = d.n_kv_heads * hd, qkv_dim = qdim + 2 * kvdim, F = d.d_ffn;
+    float* x = c->at<float>(c->lay.x);
+    float* qkv = c->at<float>(c->lay.qkv);
+    float* attn_o = c->at<float>(c->lay.attn_o);
+    float* act = c->at<float>(c->lay.act);
+    bf16_t *s_hi = c->at<bf16_t>(c->lay.s_hi), *s_lo = c->at<bf16_t>(c->lay.s_lo);
+    bf16_t *f_hi = c->at<bf16_t>(c->lay.f_hi), *f_lo = c->at<bf16_t>(c->lay.f_lo);
+    const bool mfma = c->mfma_ok && (ncols >= 2 || !c->alu_ok);
+    const int n_wg = c->n_cu * 2;
+
+    D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, s));
+    auto dump = [&](int slot) -> int {
+        if (!hidden_dump) return 0;
+        return (int)hipMemcpyAsync(hidden_dump + (size_t)slot * dump_cols * dm, x + (size_t)dump_first * dm,
+                                   (size_t)dump_cols * dm * sizeof(float), hipMemcpyDeviceToDevice, s);
+    };
+    D3_HIP(dump(0));
+
+    // ALU path: a projection takes as many columns per launch as its input fits in LDS
+    auto alu = [&](GemvArgs g, int first, int count, int mode, bool norm) -> int {
+        const int per = (int)gemv_alu_max_cols(g.K, d.weight_dtype);
+        for (int c0 = 0; c0 < count; c0 += per) {
+            GemvArgs h = g;
+            h.x = g.x + (size_t)(first + c0) * g.x_stride;
+            h.out = g.out + (size_t)(first + c0) * g.out_stride;
+            h.ncols = count - c0 < per ? count - c0 : per;
+            int rc = launch_gemv_alu(h, d.weight_dtype, mode, norm, n_wg, s);
+            if (rc != 0) return rc;
+        }
+        return 0;
+    };
+
+    int split_len, n_splits;
+    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, &split_len, &n_splits);
+
+    for (int e = 0; e < n_ids; ++e) {
+        const int l = ids[e];
+        const d3_layer_weights& w = c->layers[l];
+        // --- attention half: x += Wo . attention(RoPE(Wq a), cache) with a = RMSNorm(x) ---
+        GemvArgs g{};
+        g.K = dm; g.eps = d.rms_eps;
+        g.w[0] = w.wq; g.w[1] = w.wk; g.w[2] = w.wv;
+        g.rows[0] = qdim; g.rows[1] = kvdim; g.rows[2] = kvdim; g.total_rows = qkv_dim;
+        g.out = qkv; g.out_stride = qkv_dim; g.ncols = ncols;
+        if (mfma) {
+            D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.attn_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
+            g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+        } else {
+            g.x = x; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
+            D3_HIP(alu(g, 0, ncols, MODE_STORE, true));
+        }
+        RopeArgs r{};
+        r.qkv = qkv;
+        r.k_cache = c->k_cache + (size_t)l * c->kv_layer_bytes();
+        r.v_cache = c->v_cache + (size_t)l * c->kv_layer_bytes();
+        r.inv_freq = c->at<double>(c->lay.inv_freq);
+        r.cm = cm; r.ncols = ncols; r.H = d.n_heads; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
+        D3_HIP(launch_rope_append(r, d.kv_dtype, s));
+        AttnArgs at{};
+        at.q = qkv; at.q_stride = qkv_dim; at.k_cache = r.k_cache; at.v_cache = r.v_cache; at.cm = cm;
+        at.ncols = ncols; at.H = d.n_heads; at.H_kv = d.n_kv_heads; at.hd = hd; at.max_seq = d.max_seq;
+        at.split_len = split_len; at.n_splits = n_splits;
+        at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml);
+        at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
+        D3_HIP(launch_attention(at, d.kv_dtype, s));
+
+        GemvArgs o{};
+        o.K = qdim; o.w[0] = w.wo; o.rows[0] = dm; o.total_rows = dm; o.out = x; o.out_stride = dm; o.ncols = ncols;
+        if (mfma) { o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim; D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s)); }
+        else { o.x = attn_o; o.x_stride = qdim; D3_HIP(alu(o, 0, ncols, MODE_RESID, false)); }
+
+        // --- SwiGLU half: x += Wd (silu(Wg m) * (Wu m)) with m = RMSNorm(x) ---
+        GemvArgs u{};
+        u.K = dm; u.eps = d.rms_eps; u.w[0] = w.w_gate; u.w[1] = w.w_up; u.rows[0] = F; u.rows[1] = F; u.total_rows = F;
+        u.out_stride = F; u.ncols = ncols;
+        GemvArgs dn{};
+        dn.K = F; dn.w[0] = w.w_down; dn.rows[0] = dm; dn.total_rows = dm; dn.out = x; dn.out_stride = dm; dn.ncols = ncols;
+        if (mfma) {
+            D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.mlp_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
+            u.x_hi = s_hi; u.x_lo = s_lo; u.x_stride = dm; u.out = nullptr; u.out_hi = f_hi; u.out_lo = f_lo;
+            D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, s));
+            dn.x_hi = f_hi; dn.x_lo = f_lo; dn.x_stride = F;
+            D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s));
+        } else {
+            u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
+            D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true));
+            dn.x = act; dn.x_stride = F;
+            D3_HIP(alu(dn, 0, ncols, MODE_RESID, false));
+        }
+        D3_HIP(dump(e + 1));
+    }
+
+    if (head) {
+        GemvArgs g{};
+        g.K = dm; g.eps = d.rms_eps; g.w[0] = c->lm_head; g.rows[0] = d.vocab; g.total_rows = d.vocab;
+        g.out = head->logits; g.out_stride = d.vocab; g.ncols = head->n_cols;
+        if (mfma) {
+            D3_HIP(launch_norm_split(x + (size_t)head->first_col * dm, dm, static_cast<const float*>(c->final_norm), d.rms_eps, dm,
+                                     head->n_cols, s_hi, s_lo, s));
+            g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+        } else {
+            g.x = x + (size_t)head->first_col * dm; g.x_stride = dm; g.gain = static_cast<const float*>(c->final_norm);
+            D3_HIP(alu(g, 0, head->n_cols, MODE_STORE, true));
+        }
+        D3_HIP(launch_argmax(head->logits, d.vocab, head->n_cols, head->tok_out, s));
+    }
+    return D3_OK;
+}
+
+}  // namespace
+
+extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32_t pos_begin, int32_t* next_tok,
+                          float* logits, float* hidden_dump, void* hip_stream) {
+    if (!ctx || !tokens || !next_tok) return fail(D3_EINVAL, "d3_prefill: NULL argument");
+    const d3_model_desc& d = ctx->desc;
+    if (B < 1 || B > d.max_batch) return fail(D3_ESHAPE, "d3_prefill: B must be in [1, %d] (got %d)", d.max_batch, B);
+    if (P < 1) return fail(D3_EINVAL, "d3_prefill: P must be >= 1 (got %d)", P);
+    if (pos_begin != 0 && !(ctx->prefilled && pos_begin == ctx->n_ctx && B == ctx->B))
+        return fail(D3_ESTATE, "d3_prefill: pos_begin must be 0 or the current row count %d with the same batch (got %d)", ctx->n_ctx, pos_begin);
+    if ((int64_t)pos_begin + P > d.max_seq) return fail(D3_ERANGE, "d3_prefill: rows [%d, %d) exceed max_seq %d", pos_begin, pos_begin + P, d.max_seq);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+    std::vector<int32_t> all(d.n_layers);
+    for (int l = 0; l < d.n_layers; ++l) all[l] = l;
+    const int chunk = (kMaxCols / B) * B;
+    const int total = B * P;
+    // position-major columns in chunks that are multiples of B: the last B columns of the last
+    // chunk are the last prompt position of every sequence
+    for (int base = 0; base < total;) {
+        const int ncols = total - base < chunk ? total - base : chunk;
+        const bool last = base + ncols == total;
+        ColMap cm{base, B, P, pos_begin};
+        HeadOut head{ncols - B, B, logits ? logits : ctx->at<float>(ctx->lay.logits), next_tok};
+        int rc = forward(ctx, tokens, cm, ncols, all.data(), d.n_layers, last ? hidden_dump : nullptr, ncols - B, B,
+                         last ? &head : nullptr, s);
+        if (rc != D3_OK) return rc;
+        base += ncols;
+    }
+    for (int p = pos_begin; p < pos_begin + P; ++p) { ctx->row_drop_begin[p] = 0; ctx->row_n_drop[p] = 0; }
+    ctx->prefilled = true;
+    ctx->B = B;
+    ctx->n_ctx = pos_begin + P;
+    ctx->last_step = 0;
+    return D3_OK;
+}
+
+extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits,
+                              float* hidden_dump, void* hip_stream) {
+    if (!ctx || !tok_in || !tok_out) return fail(D3_EINVAL, "d3_decode_step: NULL argument");
+    if (!ctx->has_plan) return fail(D3_ESTATE, "d3_decode_step: no plan set (call d3_set_plan)");
+    if (!ctx->prefilled) return fail(D3_ESTATE, "d3_decode_step: no prompt pass yet (call d3_prefill)");
+    if (step_i != ctx->last_step + 1) return fail(D3_ESTATE, "d3_decode_step: expected step %d, got %d", ctx->last_step + 1, step_i);
+    if (step_i >= ctx->n_steps) return fail(D3_ERANGE, "d3_decode_step: step %d is outside the plan of %d steps", step_i, ctx->n_steps);
+    if (ctx->n_ctx >= ctx->desc.max_seq) return fail(D3_ERANGE, "d3_decode_step: cache is full (%d rows)", ctx->n_ctx);
+    const int L = ctx->desc.n_layers, B = ctx->B;
+    const int kept = ctx->keep[step_i];
+    ColMap cm{0, B, 1, ctx->n_ctx};
+    HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
+    int rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
+                     static_cast<hipStream_t>(hip_stream));
+    if (rc != D3_OK) return rc;
+    ctx->row_drop_begin[ctx->n_ctx] = ctx->drop_begin[step_i];
+    ctx->row_n_drop[ctx->n_ctx] = L - kept;
+    ctx->n_ctx += 1;
+    ctx->last_step = step_i;
+    return D3_OK;
+}
+
+extern "C" int d3_fill_missing_kv(d3_ctx* ctx, int32_t pos_begin, int32_t pos_end, int32_t mode, void* hip_stream) {
+    if (!ctx) return fail(D3_EINVAL, "d3_fill_missing_kv: ctx is NULL");
+    if (mode != D3_FILL_COPY) return fail(D3_EINVAL, "d3_fill_missing_kv: unknown mode %d", mode);
+    if (pos_begin < 0 || pos_end < pos_begin || pos_end > ctx->n_ctx)
+        return fail(D3_ERANGE, "d3_fill_missing_kv: rows [%d, %d) are outside the %d rows written", pos_begin, pos_end, ctx->n_ctx);
+    const d3_model_desc& d = ctx->desc;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    // consecutive rows whose steps dropped the same window share one launch
+    for (int p = pos_begin; p < pos_end;) {
+        int q = p + 1;
+        while (q < pos_end && ctx->row_drop_begin[q] == ctx->row_drop_begin[p] && ctx->row_n_drop[q] == ctx->row_n_drop[p]) ++q;
+        const int first = ctx->row_drop_begin[p], n = ctx->row_n_drop[p];
+        if (n > 0) {
+            FillArgs f{};
+            f.k_cache = ctx->k_cache; f.v_cache = ctx->v_cache;
+            f.max_batch = d.max_batch; f.H_kv = d.n_kv_heads; f.max_seq = d.max_seq; f.hd = d.head_dim;
+            f.B = ctx->B; f.pos_begin = p; f.pos_end = q;
+            f.drop_begin = first; f.n_drop = n;
+            f.src = first > 0 ? first - 1 : (first + n < d.n_layers ? first + n : -1);
+            D3_HIP(launch_fill(f, d.kv_dtype, s));
+        }
+        p = q;
+    }
+    return D3_OK;
+}

@@ -1,0 +1,126 @@
+// Shared declarations of the D^3 HIP library (gfx950 only): kernel argument
+// structs, launch wrappers, small device helpers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace d3 {
+
+constexpr int kWave = 64;          // CDNA wavefront
+constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per forward pass
+constexpr int kMaxSplits = 32;     // context splits of one attention head
+
+typedef uint16_t bf16_t;           // bf16 bit pattern
+
+// Which (sequence, position, token) a column of the current pass stands for.
+// Column c has global index g = base + c; sequence g % B, row pos_begin + g / B.
+// Decode: base 0, P 1 (column b = sequence b).  Prompt pass: position-major
+// enumeration of the [B][P] prompt, so the last B columns are the last positions.
+struct ColMap {
+    int base, B, P, pos_begin;
+    __host__ __device__ int seq(int c) const { return (base + c) % B; }
+    __host__ __device__ int pos(int c) const { return pos_begin + (base + c) / B; }
+    __host__ __device__ int tok_index(int c) const { return seq(c) * P + (base + c) / B; }
+};
+
+// 16-byte streaming load of weights that are read exactly once (non-temporal: do not
+// displace the activations that live in L2)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ u32x4 load_stream16(const void* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t pair) { return __uint_as_float(pair & 0xffff0000u); }
+// round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---------------- projections ----------------
+enum GemvMode { MODE_STORE = 0, MODE_RESID = 1, MODE_SWIGLU = 2 };
+
+struct GemvArgs {
+    // activations: fp32 [ncols][x_stride] (ALU path) or bf16 hi/lo halves [.][x_stride] (MFMA path)
+    const float* x;
+    const bf16_t* x_hi;
+    const bf16_t* x_lo;
+    int x_stride;
+    const float* gain;   // RMSNorm gain [K] when the norm is fused (ALU path), else nullptr
+    float eps;
+    int K;
+    // up to three row-stacked matrices [rows[m]][K] (STORE/RESID), or {gate, up} (SWIGLU)
+    const void* w[3];
+    int rows[3];
+    int total_rows;      // output rows
+    float* out;          // fp32 [ncols][out_stride]
+    bf16_t* out_hi;      // optional split copy of the output for an MFMA consumer
+    bf16_t* out_lo;
+    int out_stride;
+    int ncols;
+};
+
+// returns hipError_t as int
+int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, int n_wg, hipStream_t s);
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s);
+size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
+
+// RMSNorm + split into bf16 hi/lo for the MFMA path: out = x / sqrt(mean(x^2)+eps) * gain
+int launch_norm_split(const float* x, int x_stride, const float* gain, float eps, int K, int ncols,
+                      bf16_t* hi, bf16_t* lo, hipStream_t s);
+
+// ---------------- the rest of a block ----------------
+int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
+                 int vocab, float* x, hipStream_t s);
+
+struct RopeArgs {
+    float* qkv;            // [ncols][(H + 2 H_kv) * hd] fp32: q rotated in place
+    void* k_cache;         // this block's [max_batch][H_kv][max_seq][hd]
+    void* v_cache;
+    const double* inv_freq;  // [hd/2]
+    ColMap cm;
+    int ncols, H, H_kv, hd, max_seq;
+};
+int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s);
+
+struct AttnArgs {
+    const float* q;        // [ncols][q_stride], rotated
+    int q_stride;
+    const void* k_cache;   // this block's cache
+    const void* v_cache;
+    ColMap cm;
+    int ncols, H, H_kv, hd, max_seq;
+    int split_len, n_splits;
+    float* part_o;         // [ncols][H][n_splits][hd]
+    float* part_ml;        // [ncols][H][n_splits][2]  (max, sum)
+    float* out;            // [ncols][H*hd]
+    bf16_t* out_hi;        // optional split copy
+    bf16_t* out_lo;
+};
+int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s);
+
+int launch_argmax(const float* logits, int vocab, int ncols, int32_t* out, hipStream_t s);
+
+struct FillArgs {
+    void* k_cache;         // whole cache [L][max_batch][H_kv][max_seq][hd]
+    void* v_cache;
+    int max_batch, H_kv, max_seq, hd;
+    int B, pos_begin, pos_end;
+    int drop_begin, n_drop, src;   // src < 0: zero fill
+};
+int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s);
+
+}  // namespace d3

@@ -1,0 +1,172 @@
+// Small kernels around the projections: embedding gather, RMSNorm + bf16 split for
+// the MFMA path, rotary embedding + KV append, greedy argmax, missing-state KV fill.
+#include "d3_common.h"
+
+namespace d3 {
+
+namespace {
+
+// ---------------- embedding gather: x[c][:] = E[token(c)][:] ----------------
+template <typename W>
+__global__ __launch_bounds__(256) void embed_kernel(const W* __restrict__ emb, const int32_t* __restrict__ tokens,
+                                                    ColMap cm, int d, int vocab, float* __restrict__ x) {
+    const int c = blockIdx.x;
+    int tok = tokens[cm.tok_index(c)];
+    tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);   // stay inside the table whatever the caller fed
+    const W* row = emb + (size_t)tok * d;
+    for (int j = threadIdx.x; j < d; j += blockDim.x) {
+        float v;
+        if (sizeof(W) == 4) v = reinterpret_cast<const float*>(row)[j];
+        else v = bf16_to_f32(reinterpret_cast<const bf16_t*>(row)[j]);
+        x[(size_t)c * d + j] = v;
+    }
+}
+
+// ---------------- RMSNorm (optional) + split into bf16 hi/lo ----------------
+__global__ __launch_bounds__(256) void norm_split_kernel(const float* __restrict__ x, int x_stride,
+                                                         const float* __restrict__ gain, float eps, int K,
+                                                         bf16_t* __restrict__ hi, bf16_t* __restrict__ lo) {
+    __shared__ float red[4];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const float* xc = x + (size_t)c * x_stride;
+    float rinv = 1.0f;
+    if (gain) {
+        float ss = 0.f;
+        for (int j = tid; j < K; j += 256) ss += xc[j] * xc[j];
+        ss = wave_sum(ss);
+        if ((tid & 63) == 0) red[tid >> 6] = ss;
+        __syncthreads();
+        rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
+    }
+    for (int j = tid; j < K; j += 256) {
+        const float v = gain ? xc[j] * rinv * gain[j] : xc[j];
+        const uint32_t h = f32_to_bf16(v);
+        hi[(size_t)c * K + j] = (bf16_t)h;
+        lo[(size_t)c * K + j] = (bf16_t)f32_to_bf16(v - bf16_to_f32(h));
+    }
+}
+
+// ---------------- rotary embedding + KV append ----------------
+// Half-split pairing: dims (j, j + hd/2) of a head turn by pos * inv_freq[j].
+template <typename T>
+__device__ __forceinline__ void store_kv(T* p, float v);
+template <> __device__ __forceinline__ void store_kv<float>(float* p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_kv<bf16_t>(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
+
+template <typename T>
+__global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
+    const int head = blockIdx.x, c = blockIdx.y, j = threadIdx.x;
+    const int half = a.hd / 2;
+    if (j >= half) return;
+    const int seq = a.cm.seq(c), pos = a.cm.pos(c);
+    float* row = a.qkv + (size_t)c * (a.H + 2 * a.H_kv) * a.hd + (size_t)head * a.hd;
+    if (head < a.H + a.H_kv) {
+        double sn, cs;
+        sincos((double)pos * a.inv_freq[j], &sn, &cs);
+        const float x0 = row[j], x1 = row[j + half];
+        const float y0 = x0 * (float)cs - x1 * (float)sn;
+        const float y1 = x0 * (float)sn + x1 * (float)cs;
+        if (head < a.H) {
+            row[j] = y0;
+            row[j + half] = y1;
+        } else {
+            T* dst = static_cast<T*>(a.k_cache) + (((size_t)seq * a.H_kv + (head - a.H)) * a.max_seq + pos) * a.hd;
+            store_kv<T>(dst + j, y0);
+            store_kv<T>(dst + j + half, y1);
+        }
+    } else {
+        T* dst = static_cast<T*>(a.v_cache) + (((size_t)seq * a.H_kv + (head - a.H - a.H_kv)) * a.max_seq + pos) * a.hd;
+        store_kv<T>(dst + j, row[j]);
+        store_kv<T>(dst + j + half, row[j + half]);
+    }
+}
+
+// ---------------- greedy argmax, lowest index on ties ----------------
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ logits, int vocab, int32_t* __restrict__ out) {
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const float* lg = logits + (size_t)c * vocab;
+    float best = -INFINITY;
+    int idx = 0x7fffffff;
+    for (int j = tid; j < vocab; j += 1024) {
+        const float v = lg[j];
+        if (v > best || (v == best && j < idx)) { best = v; idx = j; }
+    }
+    // NaN logits never win (comparisons false); an all-NaN row yields index clamp below
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+        const float ov = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(idx, o, 64);
+        if (ov > best || (ov == best && oi < idx)) { best = ov; idx = oi; }
+    }
+    if ((tid & 63) == 0) { bv[tid >> 6] = best; bi[tid >> 6] = idx; }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < idx)) { best = bv[w]; idx = bi[w]; }
+        out[c] = idx >= vocab ? 0 : idx;
+    }
+}
+
+// ---------------- missing-state fill (COPY) ----------------
+// One workgroup per (row, sequence, KV head): read the source block's head vector once,
+// write it into every dropped block.  16 bytes per lane.
+__global__ __launch_bounds__(64) void fill_kernel(FillArgs a, int bytes_per_vec) {
+    const int pos = a.pos_begin + blockIdx.x;
+    const int seq = blockIdx.y / a.H_kv, h = blockIdx.y % a.H_kv;
+    const int piece = threadIdx.x;
+    if (piece * 16 >= bytes_per_vec) return;
+    const size_t layer_stride = (size_t)a.max_batch * a.H_kv * a.max_seq * bytes_per_vec;
+    const size_t off = (((size_t)seq * a.H_kv + h) * a.max_seq + pos) * bytes_per_vec + (size_t)piece * 16;
+    char* kc = static_cast<char*>(a.k_cache);
+    char* vc = static_cast<char*>(a.v_cache);
+    uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+    if (a.src >= 0) {
+        kv = *reinterpret_cast<const uint4*>(kc + (size_t)a.src * layer_stride + off);
+        vv = *reinterpret_cast<const uint4*>(vc + (size_t)a.src * layer_stride + off);
+    }
+    for (int l = a.drop_begin; l < a.drop_begin + a.n_drop; ++l) {
+        *reinterpret_cast<uint4*>(kc + (size_t)l * layer_stride + off) = kv;
+        *reinterpret_cast<uint4*>(vc + (size_t)l * layer_stride + off) = vv;
+    }
+}
+
+}  // namespace
+
+int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
+                 int vocab, float* x, hipStream_t s) {
+    if (weight_dtype == 0)
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(ncols), dim3(256), 0, s, static_cast<const float*>(tok_emb), tokens, cm, d, vocab, x);
+    else
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(ncols), dim3(256), 0, s, static_cast<const bf16_t*>(tok_emb), tokens, cm, d, vocab, x);
+    return (int)hipGetLastError();
+}
+
+int launch_norm_split(const float* x, int x_stride, const float* gain, float eps, int K, int ncols,
+                      bf16_t* hi, bf16_t* lo, hipStream_t s) {
+    hipLaunchKernelGGL(norm_split_kernel, dim3(ncols), dim3(256), 0, s, x, x_stride, gain, eps, K, hi, lo);
+    return (int)hipGetLastError();
+}
+
+int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s) {
+    dim3 grid(a.H + 2 * a.H_kv, a.ncols);
+    if (kv_dtype == 0) hipLaunchKernelGGL(rope_append_kernel<float>, grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, s, a);
+    return (int)hipGetLastError();
+}
+
+int launch_argmax(const float* logits, int vocab, int ncols, int32_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(ncols), dim3(1024), 0, s, logits, vocab, out);
+    return (int)hipGetLastError();
+}
+
+int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s) {
+    if (a.pos_end <= a.pos_begin || a.n_drop <= 0) return 0;
+    const int bytes_per_vec = a.hd * (kv_dtype == 0 ? 4 : 2);
+    dim3 grid(a.pos_end - a.pos_begin, a.B * a.H_kv);
+    hipLaunchKernelGGL(fill_kernel, grid, dim3(64), 0, s, a, bytes_per_vec);
+    return (int)hipGetLastError();
+}
+
+}  // namespace d3

@@ -1,0 +1,79 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every symbol the header
+declares, and the host-only schedule entry point agrees with the oracle bit for bit."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import d3_inputs
+import paper_2503_08524_amd as d3
+from oracle import oracle
+from paper_2503_08524_amd import build as d3_build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if d3_build.is_stale():
+        d3_build.build()
+    return d3.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "d3.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(d3_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"d3_plan_depth", "d3_prefill", "d3_decode_step", "d3_fill_missing_kv", "d3_create", "d3_destroy",
+            "d3_set_plan", "d3_workspace_size", "d3_last_error", "d3_n_ctx"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+@pytest.mark.parametrize("L,alpha,start", [(4, 0.97, 2), (32, 0.995, 19), (32, 0.99, 19), (40, 0.995, 24), (80, 0.995, 48),
+                                           (32, 1.0, 19), (32, 0.8, 0), (80, 0.9999, 16), (40, 0.9, 39)])
+def test_plan_is_bit_exact_against_oracle(lib, L, alpha, start):
+    for min_keep in (0, 2):
+        got = d3.d3_plan_depth(L, alpha, start, min_keep, 1300)
+        ref = oracle.plan_depth(L, alpha, start, min_keep, 1300)
+        for g, r in zip(got, ref):
+            assert (g == r).all()
+
+
+def test_plan_accepts_null_outputs_and_zero_steps(lib):
+    assert lib.d3_plan_depth(8, 0.9, 3, 0, 5, None, None, None) == 0
+    assert lib.d3_plan_depth(8, 0.9, 3, 0, 0, None, None, None) == 0
+
+
+@pytest.mark.parametrize("args", [(0, 0.9, 0, 0, 4), (4, 0.0, 0, 0, 4), (4, 1.0001, 0, 0, 4), (4, float("nan"), 0, 0, 4),
+                                  (4, 0.9, 4, 0, 4), (4, 0.9, -1, 0, 4), (4, 0.9, 0, 5, 4), (4, 0.9, 0, -1, 4), (4, 0.9, 0, 0, -1)])
+def test_plan_rejects_bad_arguments(lib, args):
+    with pytest.raises(d3.D3Error) as e:
+        d3.d3_plan_depth(*args)
+    assert e.value.status == -1 and "d3_plan_depth" in str(e.value)
+
+
+def test_workspace_size_and_shape_checks(lib):
+    for s in (d3_inputs.TINY, d3_inputs.LLAMA_7B, d3_inputs.LLAMA_13B, d3_inputs.LLAMA_70B):
+        n = d3.d3_workspace_size(s, s.dtype, 8, 2048)
+        assert n > 0 and n % 256 == 0 and n < 2 ** 31
+    bad = d3_inputs.ModelShape("bad", L=2, d=256, H=4, H_kv=3, hd=64, F=688, V=1024)
+    assert d3.d3_workspace_size(bad, "bf16", 1, 64) == 0
+    assert "n_kv_heads" in lib.d3_last_error().decode()
+    bad = d3_inputs.ModelShape("bad", L=2, d=256, H=4, H_kv=4, hd=80, F=688, V=1024)
+    assert d3.d3_workspace_size(bad, "bf16", 1, 64) == 0
+    assert d3.d3_workspace_size(d3_inputs.TINY, "f32", 33, 64) == 0          # max_batch beyond 32
+
+
+def test_null_context_is_an_error_not_a_crash(lib):
+    assert lib.d3_set_plan(None, 0.9, 0, 0, 4) == -1
+    assert lib.d3_decode_step(None, None, 1, None, None, None, None) == -1
+    assert lib.d3_prefill(None, None, 1, 1, 0, None, None, None, None) == -1
+    assert lib.d3_fill_missing_kv(None, 0, 0, 0, None) == -1
+    assert lib.d3_n_ctx(None) == 0
+    assert lib.d3_destroy(None) == 0

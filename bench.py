@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the D^3 decode hot path on one MI355X.
+
+Workload (the second benchmark configuration): Llama-7B-shaped decoder, random-init bf16
+weights N(0, 0.02), batch 1, prompt of 512 uniform-random token ids, 256 greedy tokens
+generated, alpha in {0.995, 1.0, 0.99}, start block 19.
+
+One bench "step" is one request's whole generation phase: G-1 = 255 decode steps under the
+D^3 schedule (every kept block, the missing-state fill of the dropped ones, lm_head, argmax),
+tokens fed back on the device, no host synchronisation inside.  The prompt pass runs once,
+untimed; each step rewinds the cache to the prompt with d3_truncate.  `value` is decode
+tokens/s at alpha = 0.995; full depth (alpha = 1) and alpha = 0.99 are reported beside it,
+each with its algorithmic HBM bytes per token and fraction of the 8 TB/s peak.
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import d3_inputs  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0
+
+CONFIGS = {
+    # name: (shape, B, P, G, alphas (first is the headline), start fraction)
+    "tiny": (d3_inputs.TINY, 1, 16, 32, (0.97, 1.0), 0.6),
+    "7b": (d3_inputs.LLAMA_7B, 1, 512, 256, (0.995, 1.0, 0.99), 0.6),
+    "13b": (d3_inputs.LLAMA_13B, 4, 1024, 256, (0.995, 1.0), 0.6),
+    "7b-b32": (d3_inputs.LLAMA_7B, 32, 2048, 512, (0.995, 1.0), 0.6),
+    "70b": (d3_inputs.LLAMA_70B, 8, 1024, 256, (0.995, 1.0), 0.6),
+}
+
+
+def block_weight_bytes(s) -> int:
+    return s.params_per_block * (4 if s.dtype == "f32" else 2)
+
+
+def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem):
+    """HBM bytes the method must move over decode steps 1..G-1: weights of the executed blocks,
+    their KV rows read and appended, the fill of the dropped blocks, lm_head."""
+    wb = block_weight_bytes(s)
+    kv_row = 2 * s.H_kv * s.hd * kv_bytes_per_elem          # K + V of one token in one block
+    head = s.V * s.d * (4 if s.dtype == "f32" else 2)
+    total = 0
+    for i in range(1, G):
+        k, n = int(keep[i]), s.L - int(keep[i])
+        total += k * (wb + kv_row * B * (P + i) + kv_row * B) + n * 2 * kv_row * B + head
+    return total
+
+
+def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill=True):
+    """`requests` whole generation phases back to back; returns seconds (host clock around a device sync)."""
+    cur = first_tok.clone()
+    nxt = torch.zeros_like(cur)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(requests):
+        dec.truncate(P)
+        dec.set_plan(alpha, start, 0, G)
+        cur.copy_(first_tok)
+        for i in range(1, G):
+            dec.decode_step(cur, i, nxt)
+            if fill:
+                dec.fill_missing_kv(P + i - 1, P + i)
+            cur, nxt = nxt, cur
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(shape, keep_mean):
+    """The oracle (float32 build, one thread) on a one-block model of the same widths; per-block and
+    lm_head times extrapolated to the workload's average depth."""
+    from oracle import oracle
+    s1 = shape.truncated(1)
+    w = d3_inputs.make_weights(s1, 0)
+    model = oracle.OracleModel(s1, w, "f32")
+    oracle.set_threads(1, "f32")
+    seq = model.new_seq(8)
+    toks = d3_inputs.make_prompt(1, 6, s1.V, seed=3)[0]
+    t0 = time.perf_counter()
+    for p in range(4):
+        seq.forward_token(int(toks[p]), p, [0])
+    t_block = (time.perf_counter() - t0) / 4
+    t0 = time.perf_counter()
+    for p in range(4, 6):
+        seq.forward_token(int(toks[p]), p, [], want_logits=True)
+    t_head = (time.perf_counter() - t0) / 2
+    per_tok = keep_mean * t_block + t_head
+    return {"value": 1.0 / per_tok, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "sample": f"float32 oracle, 1 thread, {s1.name}: 4 block-steps ({t_block * 1e3:.0f} ms each) + 2 lm_head "
+                      f"passes ({t_head * 1e3:.0f} ms each), extrapolated to {keep_mean:.2f} blocks/token",
+            "host_cores_available": os.cpu_count()}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="7b", choices=sorted(CONFIGS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fill", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2503_08524_amd import binding
+
+    shape, B, P, G, alphas, start_frac = CONFIGS[args.config]
+    start = d3_inputs.start_layer_from_fraction(shape.L, start_frac)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    kv = "f32" if shape.dtype == "f32" else "f16"
+    weights = binding.random_weights_on_device(shape, 0, dev)
+    dec = binding.Decoder(shape, weights, B, P + G, kv_dtype=kv, device=dev)
+    prompts = torch.from_numpy(d3_inputs.make_prompt(B, P, shape.V, seed=1)).to(dev)
+
+    dec.set_plan(alphas[0], start, 0, G)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    first_tok = dec.prefill(prompts)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+
+    kv_bytes = 4 if kv == "f32" else 2
+    results = {}
+    for alpha in alphas:
+        keep, _, _ = binding.d3_plan_depth(shape.L, alpha, start, 0, G)
+        run_decode(dec, torch, first_tok, P, G, alpha, start, args.warmup, not args.no_fill)
+        secs = run_decode(dec, torch, first_tok, P, G, alpha, start, args.steps, not args.no_fill)
+        n_tok = args.steps * (G - 1) * B
+        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes) * args.steps
+        results[alpha] = {
+            "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (args.steps * (G - 1)) * 1e3,
+            "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (args.steps * (G - 1)) / 1e9,
+            "achieved_GBps": alg / secs / 1e9, "frac_of_hbm_peak": alg / secs / 1e9 / HBM_PEAK_GBPS,
+        }
+    head = results[alphas[0]]
+    if 1.0 in results:
+        for a, r in results.items():
+            r["speedup_vs_full_depth"] = r["tokens_per_s"] / results[1.0]["tokens_per_s"]
+            r["ideal_layer_count_ratio"] = shape.L / r["avg_blocks"]
+            r["ideal_byte_ratio"] = results[1.0]["algorithmic_GB_per_token_step"] / r["algorithmic_GB_per_token_step"]
+
+    # dominant kernel: the fused RMSNorm + gate/up + SiLU*mul projection (45 % of a block's weight bytes),
+    # every launch bracketed by HIP events on the launch stream, over one more full-depth request
+    dec.profile_select(binding.D3_K_GATE_UP)
+    run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, False)
+    ms, n = dec.profile_read()
+    dec.profile_select(binding.D3_K_NONE)
+    wbytes = 4 if shape.dtype == "f32" else 2
+    gate_up_bytes = 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4
+    achieved = gate_up_bytes / (ms / n * 1e-3) / 1e9 if n else 0.0
+    roofline = {"bound": "hbm", "kernel": "fused RMSNorm + gate/up + SiLU*mul projection", "achieved": achieved,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": gate_up_bytes}
+
+    out = {
+        "metric": "decode tokens/sec (D^3, alpha=%g) at the Llama-7B shape; achieved HBM GB/s beside it" % alphas[0]
+        if args.config == "7b" else "decode tokens/sec (D^3, alpha=%g)" % alphas[0],
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_token_step"] * (G - 1), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if shape.dtype == "f32" else "bf16 weights, f32 accumulate, f16 KV cache",
+        "data": "synthetic",
+        "config": {"workload": f"{shape.name} B={B} P={P} G={G} alpha={alphas[0]} start_layer={start}",
+                   "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
+                   "fill_every_step": not args.no_fill},
+        "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
+        "by_alpha": {str(a): r for a, r in results.items()},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(shape, head["avg_blocks"])
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

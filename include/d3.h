@@ -19,7 +19,7 @@
  *     therefore the executed blocks (Section 1, challenge (ii); Table 1).
  *   - Layouts: linear weights row-major [out][in], float32 or bf16; RMSNorm
  *     gains float32; KV cache [L][max_batch][H_kv][max_seq][head_dim] for K and
- *     for V (keys stored after the rotary embedding), float32 or bf16.
+ *     for V (keys stored after the rotary embedding), float32, bf16 or fp16.
  */
 #ifndef D3_H
 #define D3_H
@@ -38,14 +38,14 @@ typedef enum {
     D3_EDEVICE = -5  /* a HIP call failed */
 } d3_status;
 
-typedef enum { D3_F32 = 0, D3_BF16 = 1 } d3_dtype;
+typedef enum { D3_F32 = 0, D3_BF16 = 1, D3_F16 = 2 } d3_dtype;
 typedef enum { D3_FILL_COPY = 0 } d3_fill_mode;
 
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rms_eps, rope_base;
-    int32_t weight_dtype; /* d3_dtype of every linear weight and the embedding table */
-    int32_t kv_dtype;     /* d3_dtype of the KV cache */
+    int32_t weight_dtype; /* D3_F32 or D3_BF16: every linear weight and the embedding table */
+    int32_t kv_dtype;     /* D3_F32, D3_BF16 or D3_F16 (IEEE half, values clamped to +-65504): the KV cache */
     int32_t max_batch, max_seq;
 } d3_model_desc;
 
@@ -135,6 +135,25 @@ int d3_fill_missing_kv(d3_ctx *ctx, int32_t pos_begin, int32_t pos_end, int32_t 
 
 /* Current number of cache rows per sequence. */
 int32_t d3_n_ctx(const d3_ctx *ctx);
+
+/* Forget cache rows [n_rows, n_ctx): the next decode step writes row n_rows.
+ * Used to re-run the generation phase on the same prompt (Section 3.1) without a
+ * new prompt pass.  Resets the step counter (next decode step is 1).  Host only.
+ * D3_ERANGE unless 1 <= n_rows <= n_ctx. */
+int d3_truncate(d3_ctx *ctx, int32_t n_rows);
+
+/* Measurement aid: per-launch timing of one kernel class with HIP events recorded
+ * on the caller's stream (the projections dominate the step: "computational cost
+ * scales linearly with the number of decoder blocks", Section 1).  While a class is
+ * selected, every launch of it is bracketed by two events (at most 16384 launches
+ * are recorded; further ones run untimed).  d3_profile_read synchronises on the
+ * recorded events, returns their summed duration and count, and clears them.
+ * Selecting D3_K_NONE switches the bracketing off. */
+typedef enum {
+    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6
+} d3_kernel_class;
+int d3_profile_select(d3_ctx *ctx, int32_t kernel_class);
+int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
 
 #ifdef __cplusplus
 }

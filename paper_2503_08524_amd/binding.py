@@ -13,8 +13,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB: Optional[C.CDLL] = None
 
-D3_F32, D3_BF16 = 0, 1
+D3_F32, D3_BF16, D3_F16 = 0, 1, 2
 D3_FILL_COPY = 0
+D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD = range(7)
 
 
 class D3Error(RuntimeError):
@@ -61,6 +62,9 @@ def load_library() -> C.CDLL:
         lib.d3_fill_missing_kv.argtypes = [vp, i32, i32, i32, vp]
         lib.d3_n_ctx.argtypes = [vp]
         lib.d3_n_ctx.restype = i32
+        lib.d3_truncate.argtypes = [vp, i32]
+        lib.d3_profile_select.argtypes = [vp, i32]
+        lib.d3_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _LIB = lib
     return _LIB
 
@@ -81,7 +85,7 @@ def d3_plan_depth(L: int, alpha: float, start_layer: int, min_keep: int, n_steps
 
 
 def _desc(shape, kv_dtype: str, max_batch: int, max_seq: int) -> _ModelDesc:
-    dt = {"f32": D3_F32, "bf16": D3_BF16}
+    dt = {"f32": D3_F32, "bf16": D3_BF16, "f16": D3_F16}
     return _ModelDesc(shape.L, shape.d, shape.H, shape.H_kv, shape.hd, shape.F, shape.V, float(shape.eps),
                       float(shape.rope_base), dt[shape.dtype], dt[kv_dtype], max_batch, max_seq)
 
@@ -99,7 +103,9 @@ class Decoder:
     """One d3_ctx plus the device buffers it borrows (all torch tensors on one GPU).
 
     weights: dict like d3_inputs.make_weights but of torch CUDA tensors
-    (float32, or bfloat16 for bf16 models; gains float32)."""
+    (float32, or bfloat16 for bf16 models; gains float32).  kv_dtype: "f32", "bf16"
+    or "f16"; default f32 for fp32 models, else f16 (same bytes as bf16, three more
+    mantissa bits, which the logit tolerance needs at full depth)."""
 
     def __init__(self, shape, weights: Dict[str, object], max_batch: int, max_seq: int, kv_dtype: Optional[str] = None,
                  device: str = "cuda:0"):
@@ -108,14 +114,14 @@ class Decoder:
         self.lib = load_library()
         self.shape = shape
         self.device = torch.device(device)
-        self.kv_dtype = kv_dtype or shape.dtype
+        self.kv_dtype = kv_dtype or ("f32" if shape.dtype == "f32" else "f16")
         self.max_batch, self.max_seq = max_batch, max_seq
         self.weights = weights                       # keep the tensors alive
         desc = _desc(shape, self.kv_dtype, max_batch, max_seq)
         ws_bytes = int(self.lib.d3_workspace_size(C.byref(desc)))
         if ws_bytes == 0:
             _check(-2)
-        tdt = torch.float32 if self.kv_dtype == "f32" else torch.bfloat16
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[self.kv_dtype]
         kv_shape = (shape.L, max_batch, shape.H_kv, max_seq, shape.hd)
         with torch.cuda.device(self.device):
             self.k_cache = torch.zeros(kv_shape, dtype=tdt, device=self.device)
@@ -162,6 +168,18 @@ class Decoder:
 
     def fill_missing_kv(self, pos_begin: int, pos_end: int, mode: int = D3_FILL_COPY) -> None:
         _check(self.lib.d3_fill_missing_kv(self.ctx, pos_begin, pos_end, mode, self._stream()))
+
+    def truncate(self, n_rows: int) -> None:
+        _check(self.lib.d3_truncate(self.ctx, n_rows))
+
+    def profile_select(self, kernel_class: int) -> None:
+        _check(self.lib.d3_profile_select(self.ctx, kernel_class))
+
+    def profile_read(self):
+        """(summed milliseconds, launches) of the selected kernel class since the last read."""
+        ms, n = C.c_double(), C.c_int64()
+        _check(self.lib.d3_profile_read(self.ctx, C.byref(ms), C.byref(n)))
+        return ms.value, n.value
 
     @property
     def n_ctx(self) -> int:

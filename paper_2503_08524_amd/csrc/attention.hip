@@ -25,6 +25,16 @@ template <> struct KvVec<bf16_t> {
     }
 };
 
+template <> struct KvVec<f16_t> {
+    static constexpr int N = 8;
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+        const half8 h = __builtin_bit_cast(half8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (float)h[e];
+    }
+};
+
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     constexpr int EPL = KvVec<T>::N;       // elements per lane per 16-byte load
@@ -175,13 +185,15 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(AttnArgs a) {
 int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s) {
     dim3 grid(a.n_splits, a.H, a.ncols);
     const size_t lds = (size_t)a.split_len * sizeof(float);
-    if (kv_dtype == 0) {
-        if (a.hd == 64) hipLaunchKernelGGL((attn_partial_kernel<float, 64>), grid, dim3(256), lds, s, a);
-        else hipLaunchKernelGGL((attn_partial_kernel<float, 128>), grid, dim3(256), lds, s, a);
-    } else {
-        if (a.hd == 64) hipLaunchKernelGGL((attn_partial_kernel<bf16_t, 64>), grid, dim3(256), lds, s, a);
-        else hipLaunchKernelGGL((attn_partial_kernel<bf16_t, 128>), grid, dim3(256), lds, s, a);
-    }
+#define D3_ATTN(T)                                                                                      \
+    do {                                                                                                \
+        if (a.hd == 64) hipLaunchKernelGGL((attn_partial_kernel<T, 64>), grid, dim3(256), lds, s, a);   \
+        else hipLaunchKernelGGL((attn_partial_kernel<T, 128>), grid, dim3(256), lds, s, a);             \
+    } while (0)
+    if (kv_dtype == 0) D3_ATTN(float);
+    else if (kv_dtype == 1) D3_ATTN(bf16_t);
+    else D3_ATTN(f16_t);
+#undef D3_ATTN
     int rc = (int)hipGetLastError();
     if (rc != 0) return rc;
     hipLaunchKernelGGL(attn_combine_kernel, dim3(a.H, a.ncols), dim3(128), 0, s, a);

@@ -45,8 +45,9 @@ int check_desc(const d3_model_desc* d) {
     if (d->vocab % 2 != 0) return fail(D3_ESHAPE, "vocab must be even (got %d)", d->vocab);
     if (d->max_batch < 1 || d->max_batch > kMaxCols) return fail(D3_ESHAPE, "max_batch must be in [1, %d] (got %d)", kMaxCols, d->max_batch);
     if (d->max_seq < 1 || d->max_seq > kMaxSplits * 8192) return fail(D3_ESHAPE, "max_seq must be in [1, %d]", kMaxSplits * 8192);
-    if ((d->weight_dtype != D3_F32 && d->weight_dtype != D3_BF16) || (d->kv_dtype != D3_F32 && d->kv_dtype != D3_BF16))
-        return fail(D3_EINVAL, "weight_dtype and kv_dtype must be D3_F32 or D3_BF16");
+    if (d->weight_dtype != D3_F32 && d->weight_dtype != D3_BF16) return fail(D3_EINVAL, "weight_dtype must be D3_F32 or D3_BF16");
+    if (d->kv_dtype != D3_F32 && d->kv_dtype != D3_BF16 && d->kv_dtype != D3_F16)
+        return fail(D3_EINVAL, "kv_dtype must be D3_F32, D3_BF16 or D3_F16");
     if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(D3_EINVAL, "rms_eps must be >= 0 and rope_base > 1");
     if (!alu_fits(*d) && !mfma_fits(*d))
         return fail(D3_ESHAPE, "d_model / d_ffn fit neither the LDS-staged GEMV nor the matrix-core path");
@@ -96,9 +97,14 @@ struct d3_ctx {
     int B, n_ctx, last_step;
     std::vector<int32_t> row_drop_begin, row_n_drop;   // per cache row: what the step that wrote it dropped
 
+    // per-launch timing of one kernel class
+    int prof_class;
+    std::vector<hipEvent_t> prof_events;   // pairs (start, stop), created on first use
+    size_t prof_used;                      // events recorded so far
+
     template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(ws + off); }
     size_t kv_layer_bytes() const {
-        return (size_t)desc.max_batch * desc.n_kv_heads * desc.max_seq * desc.head_dim * (desc.kv_dtype == D3_F32 ? 4 : 2);
+        return (size_t)desc.max_batch * desc.n_kv_heads * desc.max_seq * desc.head_dim * kv_elem_bytes(desc.kv_dtype);
     }
 };
 
@@ -148,6 +154,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->n_cu = prop.multiProcessorCount;
     c->mfma_ok = mfma_fits(*desc);
     c->alu_ok = alu_fits(*desc);
+    c->prof_class = D3_K_NONE; c->prof_used = 0;
     c->has_plan = false; c->n_steps = 0;
     c->prefilled = false; c->B = 0; c->n_ctx = 0; c->last_step = 0;
     c->row_drop_begin.assign(desc->max_seq, 0);
@@ -163,6 +170,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
 }
 
 extern "C" int d3_destroy(d3_ctx* ctx) {
+    if (ctx)
+        for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     delete ctx;
     return D3_OK;
 }
@@ -185,6 +194,22 @@ extern "C" int d3_set_plan(d3_ctx* ctx, double alpha, int32_t start_layer, int32
 }
 
 namespace {
+
+constexpr size_t kMaxProfEvents = 2 * 16384;
+
+// Brackets the launches issued during its lifetime with two events when `cls` is the selected class.
+struct Timed {
+    d3_ctx* c; hipStream_t s; bool on;
+    Timed(d3_ctx* ctx, int cls, hipStream_t stream) : c(ctx), s(stream), on(false) {
+        if (c->prof_class != cls || c->prof_used + 2 > c->prof_events.size()) return;
+        on = hipEventRecord(c->prof_events[c->prof_used], s) == hipSuccess;
+    }
+    ~Timed() {
+        if (!on) return;
+        (void)hipEventRecord(c->prof_events[c->prof_used + 1], s);
+        c->prof_used += 2;
+    }
+};
 
 struct HeadOut {       // what to do after the last block
     int first_col, n_cols;      // columns that get logits
@@ -258,9 +283,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         if (mfma) {
             D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.attn_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
             g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            Timed t(c, D3_K_QKV, s);
             D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
         } else {
             g.x = x; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
+            Timed t(c, D3_K_QKV, s);
             D3_HIP(alu(g, 0, ncols, MODE_STORE, true));
         }
         RopeArgs r{};
@@ -276,12 +303,18 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         at.split_len = split_len; at.n_splits = n_splits;
         at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml);
         at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
-        D3_HIP(launch_attention(at, d.kv_dtype, s));
+        {
+            Timed t(c, D3_K_ATTN, s);
+            D3_HIP(launch_attention(at, d.kv_dtype, s));
+        }
 
         GemvArgs o{};
         o.K = qdim; o.w[0] = w.wo; o.rows[0] = dm; o.total_rows = dm; o.out = x; o.out_stride = dm; o.ncols = ncols;
-        if (mfma) { o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim; D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s)); }
-        else { o.x = attn_o; o.x_stride = qdim; D3_HIP(alu(o, 0, ncols, MODE_RESID, false)); }
+        {
+            Timed t(c, D3_K_OPROJ, s);
+            if (mfma) { o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim; D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s)); }
+            else { o.x = attn_o; o.x_stride = qdim; D3_HIP(alu(o, 0, ncols, MODE_RESID, false)); }
+        }
 
         // --- SwiGLU half: x += Wd (silu(Wg m) * (Wu m)) with m = RMSNorm(x) ---
         GemvArgs u{};
@@ -292,14 +325,14 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         if (mfma) {
             D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.mlp_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
             u.x_hi = s_hi; u.x_lo = s_lo; u.x_stride = dm; u.out = nullptr; u.out_hi = f_hi; u.out_lo = f_lo;
-            D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, s));
+            { Timed t(c, D3_K_GATE_UP, s); D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, s)); }
             dn.x_hi = f_hi; dn.x_lo = f_lo; dn.x_stride = F;
-            D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s));
+            { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s)); }
         } else {
             u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
-            D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true));
+            { Timed t(c, D3_K_GATE_UP, s); D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true)); }
             dn.x = act; dn.x_stride = F;
-            D3_HIP(alu(dn, 0, ncols, MODE_RESID, false));
+            { Timed t(c, D3_K_DOWN, s); D3_HIP(alu(dn, 0, ncols, MODE_RESID, false)); }
         }
         D3_HIP(dump(e + 1));
     }
@@ -312,9 +345,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             D3_HIP(launch_norm_split(x + (size_t)head->first_col * dm, dm, static_cast<const float*>(c->final_norm), d.rms_eps, dm,
                                      head->n_cols, s_hi, s_lo, s));
             g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            Timed t(c, D3_K_LM_HEAD, s);
             D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
         } else {
             g.x = x + (size_t)head->first_col * dm; g.x_stride = dm; g.gain = static_cast<const float*>(c->final_norm);
+            Timed t(c, D3_K_LM_HEAD, s);
             D3_HIP(alu(g, 0, head->n_cols, MODE_STORE, true));
         }
         D3_HIP(launch_argmax(head->logits, d.vocab, head->n_cols, head->tok_out, s));
@@ -404,5 +439,45 @@ extern "C" int d3_fill_missing_kv(d3_ctx* ctx, int32_t pos_begin, int32_t pos_en
         }
         p = q;
     }
+    return D3_OK;
+}
+
+extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
+    if (!ctx) return fail(D3_EINVAL, "d3_truncate: ctx is NULL");
+    if (!ctx->prefilled) return fail(D3_ESTATE, "d3_truncate: no prompt pass yet");
+    if (n_rows < 1 || n_rows > ctx->n_ctx) return fail(D3_ERANGE, "d3_truncate: n_rows must be in [1, %d] (got %d)", ctx->n_ctx, n_rows);
+    ctx->n_ctx = n_rows;
+    ctx->last_step = 0;
+    return D3_OK;
+}
+
+extern "C" int d3_profile_select(d3_ctx* ctx, int32_t kernel_class) {
+    if (!ctx) return fail(D3_EINVAL, "d3_profile_select: ctx is NULL");
+    if (kernel_class < D3_K_NONE || kernel_class > D3_K_LM_HEAD) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
+    if (kernel_class != D3_K_NONE && ctx->prof_events.empty()) {
+        ctx->prof_events.reserve(kMaxProfEvents);
+        for (size_t i = 0; i < kMaxProfEvents; ++i) {
+            hipEvent_t e;
+            D3_HIP(hipEventCreate(&e));
+            ctx->prof_events.push_back(e);
+        }
+    }
+    ctx->prof_class = kernel_class;
+    ctx->prof_used = 0;
+    return D3_OK;
+}
+
+extern "C" int d3_profile_read(d3_ctx* ctx, double* total_ms, int64_t* launches) {
+    if (!ctx || !total_ms || !launches) return fail(D3_EINVAL, "d3_profile_read: NULL argument");
+    double sum = 0.0;
+    for (size_t i = 0; i + 1 < ctx->prof_used; i += 2) {
+        float ms = 0.f;
+        D3_HIP(hipEventSynchronize(ctx->prof_events[i + 1]));
+        D3_HIP(hipEventElapsedTime(&ms, ctx->prof_events[i], ctx->prof_events[i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = (int64_t)(ctx->prof_used / 2);
+    ctx->prof_used = 0;
     return D3_OK;
 }

@@ -11,6 +11,10 @@ constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per for
 constexpr int kMaxSplits = 32;     // context splits of one attention head
 
 typedef uint16_t bf16_t;           // bf16 bit pattern
+typedef _Float16 f16_t;            // IEEE half (KV cache only)
+
+// bytes per KV-cache element for a d3_dtype value (0 f32, 1 bf16, 2 f16)
+inline int kv_elem_bytes(int kv_dtype) { return kv_dtype == 0 ? 4 : 2; }
 
 // Which (sequence, position, token) a column of the current pass stands for.
 // Column c has global index g = base + c; sequence g % B, row pos_begin + g / B.

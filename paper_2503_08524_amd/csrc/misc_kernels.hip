@@ -52,6 +52,7 @@ template <typename T>
 __device__ __forceinline__ void store_kv(T* p, float v);
 template <> __device__ __forceinline__ void store_kv<float>(float* p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_kv<bf16_t>(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
+template <> __device__ __forceinline__ void store_kv<f16_t>(f16_t* p, float v) { *p = (f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
 
 template <typename T>
 __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
@@ -152,7 +153,8 @@ int launch_norm_split(const float* x, int x_stride, const float* gain, float eps
 int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s) {
     dim3 grid(a.H + 2 * a.H_kv, a.ncols);
     if (kv_dtype == 0) hipLaunchKernelGGL(rope_append_kernel<float>, grid, dim3(64), 0, s, a);
-    else hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, s, a);
+    else if (kv_dtype == 1) hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL(rope_append_kernel<f16_t>, grid, dim3(64), 0, s, a);
     return (int)hipGetLastError();
 }
 
@@ -163,7 +165,7 @@ int launch_argmax(const float* logits, int vocab, int ncols, int32_t* out, hipSt
 
 int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s) {
     if (a.pos_end <= a.pos_begin || a.n_drop <= 0) return 0;
-    const int bytes_per_vec = a.hd * (kv_dtype == 0 ? 4 : 2);
+    const int bytes_per_vec = a.hd * kv_elem_bytes(kv_dtype);
     dim3 grid(a.pos_end - a.pos_begin, a.B * a.H_kv);
     hipLaunchKernelGGL(fill_kernel, grid, dim3(64), 0, s, a, bytes_per_vec);
     return (int)hipGetLastError();

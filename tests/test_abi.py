@@ -60,7 +60,7 @@ def test_plan_rejects_bad_arguments(lib, args):
 
 def test_workspace_size_and_shape_checks(lib):
     for s in (d3_inputs.TINY, d3_inputs.LLAMA_7B, d3_inputs.LLAMA_13B, d3_inputs.LLAMA_70B):
-        n = d3.d3_workspace_size(s, s.dtype, 8, 2048)
+        n = d3.d3_workspace_size(s, "f16" if s.dtype == "bf16" else "f32", 8, 2048)
         assert n > 0 and n % 256 == 0 and n < 2 ** 31
     bad = d3_inputs.ModelShape("bad", L=2, d=256, H=4, H_kv=3, hd=64, F=688, V=1024)
     assert d3.d3_workspace_size(bad, "bf16", 1, 64) == 0

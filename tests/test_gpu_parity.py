@@ -26,7 +26,7 @@ def _run(shape, B, P, G, alpha, start, kv_dtype=None, forced_seed=None, check_to
     forced = None if forced_seed is None else _forced(B, G, shape.V, forced_seed)
     print(f"case {shape.name} B={B} P={P} G={G} alpha={alpha} start={start} kv={kv_dtype}", flush=True)
     gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, kv_dtype=kv_dtype, **kw)
-    _, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced)
+    _, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, min_keep=kw.get("min_keep", 0))
     wl, wh = helpers.compare(gpu, gens, G, check_tokens=check_tokens)
     print(f"  worst logit abs err {wl:.3e}, worst hidden rel L2 {wh:.3e}", flush=True)
     return gpu, gens
@@ -54,9 +54,9 @@ def test_small_bf16_matrix_core_path(B, P):
     _run(SMALL_BF16, B, P, 8, 0.9, 2, forced_seed=7)
 
 
-@pytest.mark.parametrize("B", [1, 3])
-def test_small_gqa(B):
-    _run(SMALL_GQA, B, 37, 6, 0.8, 1, forced_seed=8)
+@pytest.mark.parametrize("B,kv", [(1, "f16"), (3, "f16"), (2, "bf16"), (2, "f32")])
+def test_small_gqa(B, kv):
+    _run(SMALL_GQA, B, 37, 6, 0.8, 1, forced_seed=8, kv_dtype=kv)
 
 
 def test_long_context_spans_several_attention_splits():

@@ -150,10 +150,22 @@ int d3_truncate(d3_ctx *ctx, int32_t n_rows);
  * recorded events, returns their summed duration and count, and clears them.
  * Selecting D3_K_NONE switches the bracketing off. */
 typedef enum {
-    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6
+    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6,
+    D3_K_STEP = 7 /* the persistent one-launch decode step (batch 1) */
 } d3_kernel_class;
 int d3_profile_select(d3_ctx *ctx, int32_t kernel_class);
 int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
+
+/* Batch-1 decode steps of bf16 models with head_dim 128 run as ONE persistent cooperative
+ * launch per step whose phases are separated by software grid barriers (Section 3.4: the step's
+ * cost is the kept blocks' weights, so launch overheads between projections are what is left to
+ * remove).  Every barrier wait is bounded; if one ever expires the step's outputs are invalid.
+ * d3_sync_check synchronises the stream and reports that case as D3_EDEVICE (and re-arms the
+ * barrier); D3_OK otherwise.  d3_uses_persistent_step returns the launch's workgroup count, or 0
+ * when the context decodes with one launch per projection (other shapes, batch > 1, or the
+ * environment variable D3_PERSISTENT=0 at d3_create). */
+int d3_sync_check(d3_ctx *ctx, void *hip_stream);
+int d3_uses_persistent_step(const d3_ctx *ctx);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ _LIB: Optional[C.CDLL] = None
 
 D3_F32, D3_BF16, D3_F16 = 0, 1, 2
 D3_FILL_COPY = 0
-D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD = range(7)
+D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD, D3_K_STEP = range(8)
 
 
 class D3Error(RuntimeError):
@@ -63,6 +63,8 @@ def load_library() -> C.CDLL:
         lib.d3_n_ctx.argtypes = [vp]
         lib.d3_n_ctx.restype = i32
         lib.d3_truncate.argtypes = [vp, i32]
+        lib.d3_sync_check.argtypes = [vp, vp]
+        lib.d3_uses_persistent_step.argtypes = [vp]
         lib.d3_profile_select.argtypes = [vp, i32]
         lib.d3_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _LIB = lib
@@ -168,6 +170,14 @@ class Decoder:
 
     def fill_missing_kv(self, pos_begin: int, pos_end: int, mode: int = D3_FILL_COPY) -> None:
         _check(self.lib.d3_fill_missing_kv(self.ctx, pos_begin, pos_end, mode, self._stream()))
+
+    def sync_check(self) -> None:
+        """Synchronise the stream; raises if a persistent decode step gave up at a grid barrier."""
+        _check(self.lib.d3_sync_check(self.ctx, self._stream()))
+
+    @property
+    def persistent_workgroups(self) -> int:
+        return int(self.lib.d3_uses_persistent_step(self.ctx))
 
     def truncate(self, n_rows: int) -> None:
         _check(self.lib.d3_truncate(self.ctx, n_rows))

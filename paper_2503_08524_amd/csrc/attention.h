@@ -1,0 +1,199 @@
+// Device-side body of the decode attention (see attention.hip): one (column, head, context split)
+// per call by a 256-thread workgroup, plus the merge of the splits by whichever split arrives last.
+#pragma once
+#include "d3_common.h"
+
+namespace d3 {
+
+template <typename T> struct KvVec;
+template <> struct KvVec<float> {
+    static constexpr int N = 4;
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[4]) {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+    }
+    static __device__ __forceinline__ float round(float v) { return v; }
+};
+template <> struct KvVec<bf16_t> {
+    static constexpr int N = 8;
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+        f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+        f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+    }
+    static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+};
+template <> struct KvVec<f16_t> {
+    static constexpr int N = 8;
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
+        const half8 h = __builtin_bit_cast(half8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (float)h[e];
+    }
+    static __device__ __forceinline__ float round(float v) { return (float)(f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
+};
+
+template <int HD>
+struct AttnShared {
+    float red_m[4], red_s[4];
+    float osum[4][HD];
+    int is_last;
+};
+
+// FUSED: the call runs inside a kernel that also produced q and the newest K/V row in this launch:
+// q and that row are read from the fp32 projection buffer with agent-scope loads (the row rounded
+// to the cache's element type, i.e. exactly what later steps will read back), and the merged
+// output is published with agent-scope stores.
+template <typename T, int HD, bool FUSED>
+__device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, int c, float* sc, AttnShared<HD>& sh) {
+    constexpr int EPL = KvVec<T>::N;       // elements per lane per 16-byte load
+    constexpr int LPR = HD / EPL;          // lanes that share one cache row
+    constexpr int RPW = 64 / LPR;          // rows per wave per load
+    constexpr int RPB = RPW * 4;           // rows per workgroup per load
+    constexpr int U = 4;                   // loads in flight per lane
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
+    const int j0 = split * a.split_len;
+    const int j1 = min(j0 + a.split_len, ctx);
+    const size_t pidx = ((size_t)c * a.H + h) * a.n_splits + split;
+    if (j0 >= j1) return;                  // nothing of this column's context falls in this split
+    const int n_live = (ctx + a.split_len - 1) / a.split_len;   // splits of this column that hold rows
+    const int n = j1 - j0;
+    const int kvh = h / (a.H / a.H_kv);
+    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const T* Kb = static_cast<const T*>(a.k_cache) + head_off;
+    const T* Vb = static_cast<const T*>(a.v_cache) + head_off;
+    const int sub = lane % LPR, rg = lane / LPR;
+    // FUSED: the newest row (ctx - 1) of this column, k then v, inside the projection buffer
+    const float* cur_k = a.q + (size_t)c * a.q_stride + (size_t)(a.H + kvh) * HD + sub * EPL;
+    const float* cur_v = cur_k + (size_t)a.H_kv * HD;
+
+    float qv[EPL];
+    {
+        const float scale = 1.0f / sqrtf((float)HD);
+        const float* qp = a.q + (size_t)c * a.q_stride + (size_t)h * HD + sub * EPL;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) qv[e] = (FUSED ? ld_agent(qp + e) : qp[e]) * scale;
+    }
+
+    // ---- scores ----
+    const int iters = (n + RPB - 1) / RPB;
+    float lmax = -INFINITY;
+    for (int it = 0; it < iters; it += U) {
+        uint4 kv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int jc = j < j1 ? j : j1 - 1;
+            kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            float kf[EPL];
+            KvVec<T>::unpack(kv[u], kf);
+            if (FUSED && j == ctx - 1) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
+            }
+            float s = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
+#pragma unroll
+            for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+            if (j < j1) {
+                if (sub == 0) sc[j - j0] = s;
+                lmax = fmaxf(lmax, s);
+            }
+        }
+    }
+    lmax = wave_max(lmax);
+    if (lane == 0) sh.red_m[wave] = lmax;
+    __syncthreads();
+    const float m = fmaxf(fmaxf(sh.red_m[0], sh.red_m[1]), fmaxf(sh.red_m[2], sh.red_m[3]));
+
+    // ---- probabilities (relative to this split's max) ----
+    float lsum = 0.f;
+    for (int t = tid; t < n; t += 256) {
+        const float p = expf(sc[t] - m);
+        sc[t] = p;
+        lsum += p;
+    }
+    lsum = wave_sum(lsum);
+    if (lane == 0) sh.red_s[wave] = lsum;
+    __syncthreads();
+
+    // ---- weighted sum of V rows ----
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    for (int it = 0; it < iters; it += U) {
+        uint4 vv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int jc = j < j1 ? j : j1 - 1;
+            vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const float p = j < j1 ? sc[j - j0] : 0.f;
+            float vf[EPL];
+            KvVec<T>::unpack(vv[u], vf);
+            if (FUSED && j == ctx - 1) {
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
+            }
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+#pragma unroll
+        for (int o = LPR; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
+    }
+    if (rg == 0) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) sh.osum[wave][sub * EPL + e] = acc[e];
+    }
+    __syncthreads();
+    if (tid < HD) st_agent(&a.part_o[pidx * HD + tid], sh.osum[0][tid] + sh.osum[1][tid] + sh.osum[2][tid] + sh.osum[3][tid]);
+    if (tid == 0) {
+        st_agent(&a.part_ml[pidx * 2], m);
+        st_agent(&a.part_ml[pidx * 2 + 1], sh.red_s[0] + sh.red_s[1] + sh.red_s[2] + sh.red_s[3]);
+    }
+
+    // ---- the split that arrives last merges all splits of this (column, head) ----
+    wait_stores();                                     // this split's partial has reached the coherence point
+    __syncthreads();
+    if (tid == 0) {
+        const int done = atomicAdd(&a.tickets[c * a.H + h], 1);
+        sh.is_last = done == n_live - 1;
+        if (sh.is_last) __hip_atomic_store(&a.tickets[c * a.H + h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
+    }
+    __syncthreads();
+    if (!sh.is_last) return;
+    if (tid < HD) {
+        const size_t p0 = ((size_t)c * a.H + h) * a.n_splits;
+        float gm = -INFINITY;
+        for (int s = 0; s < n_live; ++s) gm = fmaxf(gm, ld_agent(&a.part_ml[(p0 + s) * 2]));
+        float l = 0.f, o = 0.f;
+        for (int s = 0; s < n_live; ++s) {
+            const float w = expf(ld_agent(&a.part_ml[(p0 + s) * 2]) - gm);
+            l += ld_agent(&a.part_ml[(p0 + s) * 2 + 1]) * w;
+            o += ld_agent(&a.part_o[(p0 + s) * HD + tid]) * w;
+        }
+        const float r = o / l;
+        const size_t oi = (size_t)c * a.H * HD + (size_t)h * HD + tid;
+        if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
+        if (a.out_hi) {
+            const uint32_t hb = f32_to_bf16(r);
+            a.out_hi[oi] = (bf16_t)hb;
+            a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+        }
+    }
+}
+
+}  // namespace d3

@@ -2,12 +2,14 @@
 // that launches only the blocks the schedule keeps (Section 3.4).  All device memory is the
 // caller's; this file owns host state only.
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
 
 #include "../../include/d3.h"
 #include "d3_common.h"
+#include "decode_mega.h"
 #include "d3_error.h"
 
 using namespace d3;
@@ -20,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, layer_table, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -67,13 +69,19 @@ Layout make_layout(const d3_model_desc& d) {
     l.act = take(C * (size_t)d.d_ffn * 4);
     l.part_o = take(C * d.n_heads * kMaxSplits * (size_t)d.head_dim * 4);
     l.part_ml = take(C * d.n_heads * kMaxSplits * 2 * 4);
+    l.tickets = take(C * d.n_heads * 4);
     l.logits = take(C * (size_t)d.vocab * 4);
     l.s_hi = take(C * s_dim * 2);
     l.s_lo = take(C * s_dim * 2);
     l.f_hi = take(C * (size_t)d.d_ffn * 2);
     l.f_lo = take(C * (size_t)d.d_ffn * 2);
     l.inv_freq = take((size_t)d.head_dim / 2 * 8);
+    l.rope_cs = take(C * (size_t)d.head_dim / 2 * 8);
     l.layer_table = take((size_t)kMaxPlanSteps * d.n_layers * 4);
+    l.layer_ptrs = take((size_t)d.n_layers * sizeof(d3_layer_weights));
+    l.barrier = take(512 * 4);
+    l.cand_val = take(4096 * 4);
+    l.cand_idx = take(4096 * 4);
     l.total = o;
     return l;
 }
@@ -87,6 +95,7 @@ struct d3_ctx {
     char *k_cache, *v_cache, *ws;
     Layout lay;
     int n_cu;
+    int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 2)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
     bool has_plan;
@@ -97,6 +106,10 @@ struct d3_ctx {
     int B, n_ctx, last_step;
     std::vector<int32_t> row_drop_begin, row_n_drop;   // per cache row: what the step that wrote it dropped
 
+    // persistent one-launch decode step (batch 1, bf16 weights, head_dim 128)
+    bool mega_ok;
+    int mega_wgs;                 // workgroups of the cooperative launch
+    unsigned bar_epoch;           // grid barriers completed so far
     // per-launch timing of one kernel class
     int prof_class;
     std::vector<hipEvent_t> prof_events;   // pairs (start, stop), created on first use
@@ -152,6 +165,11 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->k_cache = static_cast<char*>(k_cache); c->v_cache = static_cast<char*>(v_cache); c->ws = static_cast<char*>(workspace);
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
+    c->gemv_wgs_per_cu = 2;
+    if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {
+        const int v = atoi(env);
+        if (v >= 1 && v <= 8) c->gemv_wgs_per_cu = v;
+    }
     c->mfma_ok = mfma_fits(*desc);
     c->alu_ok = alu_fits(*desc);
     c->prof_class = D3_K_NONE; c->prof_used = 0;
@@ -160,11 +178,34 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->row_drop_begin.assign(desc->max_seq, 0);
     c->row_n_drop.assign(desc->max_seq, 0);
 
+    // persistent decode step: needs the block pointer table and zeroed barrier words on the device
+    c->mega_ok = false; c->mega_wgs = 0; c->bar_epoch = 0;
+    {
+        const char* env = getenv("D3_PERSISTENT");
+        const bool want = !(env && atoi(env) == 0);
+        int per_cu = 1;
+        if (const char* e2 = getenv("D3_PERSISTENT_WGS_PER_CU")) { const int v = atoi(e2); if (v >= 1 && v <= 4) per_cu = v; }
+        if (want && desc->weight_dtype == D3_BF16 && desc->head_dim == 128 && c->alu_ok) {
+            MegaArgs probe{};
+            probe.d_model = desc->d_model; probe.H = desc->n_heads; probe.d_ffn = desc->d_ffn; probe.split_len = 8192;
+            const int fit = mega_max_workgroups(desc->kv_dtype, mega_lds_bytes(probe), c->n_cu);
+            int wgs = c->n_cu * per_cu;
+            if (wgs > fit) wgs = fit;
+            const long long waves = (long long)wgs * 4;
+            const long long most_units = desc->vocab / 2 > desc->d_ffn ? desc->vocab / 2 : desc->d_ffn;
+            if (wgs >= 8 && waves * 64 >= most_units && waves <= 4096) { c->mega_ok = true; c->mega_wgs = wgs; }
+        }
+        hipError_t e1 = hipMemcpy(c->at<d3_layer_weights>(lay.layer_ptrs), w->layers, (size_t)desc->n_layers * sizeof(d3_layer_weights), hipMemcpyHostToDevice);
+        if (e1 == hipSuccess) e1 = hipMemset(c->at<unsigned>(lay.barrier), 0, 512 * 4);
+        if (e1 != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: uploading the block table failed: %s", hipGetErrorString(e1)); }
+    }
+
     // rotary frequencies base^(-2j/hd), in binary64
     std::vector<double> inv(desc->head_dim / 2);
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
-    if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy failed: %s", hipGetErrorString(e)); }
+    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kMaxCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
+    if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
     return D3_OK;
 }
@@ -218,9 +259,9 @@ struct HeadOut {       // what to do after the last block
 };
 
 // Attention split geometry for a pass whose longest context is `ctx` rows.
-void pick_splits(const d3_ctx* c, int ncols, int ctx, int* split_len, int* n_splits) {
+void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split_len, int* n_splits) {
     const int heads = ncols * c->desc.n_heads;
-    int want = (2 * c->n_cu + heads - 1) / heads;
+    int want = (target_wgs + heads - 1) / heads;
     if (want < 1) want = 1;
     if (want > kMaxSplits) want = kMaxSplits;
     int len = ((ctx + want - 1) / want + 63) / 64 * 64;
@@ -244,9 +285,10 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     bf16_t *s_hi = c->at<bf16_t>(c->lay.s_hi), *s_lo = c->at<bf16_t>(c->lay.s_lo);
     bf16_t *f_hi = c->at<bf16_t>(c->lay.f_hi), *f_lo = c->at<bf16_t>(c->lay.f_lo);
     const bool mfma = c->mfma_ok && (ncols >= 2 || !c->alu_ok);
-    const int n_wg = c->n_cu * 2;
+    const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
 
-    D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, s));
+    float2* rope_cs = c->at<float2>(c->lay.rope_cs);
+    D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, s));
     auto dump = [&](int slot) -> int {
         if (!hidden_dump) return 0;
         return (int)hipMemcpyAsync(hidden_dump + (size_t)slot * dump_cols * dm, x + (size_t)dump_first * dm,
@@ -262,6 +304,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             h.x = g.x + (size_t)(first + c0) * g.x_stride;
             h.out = g.out + (size_t)(first + c0) * g.out_stride;
             h.ncols = count - c0 < per ? count - c0 : per;
+            h.col0 = first + c0;
             int rc = launch_gemv_alu(h, d.weight_dtype, mode, norm, n_wg, s);
             if (rc != 0) return rc;
         }
@@ -269,7 +312,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     };
 
     int split_len, n_splits;
-    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, &split_len, &n_splits);
+    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, 2 * c->n_cu, &split_len, &n_splits);
 
     for (int e = 0; e < n_ids; ++e) {
         const int l = ids[e];
@@ -280,28 +323,32 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         g.w[0] = w.wq; g.w[1] = w.wk; g.w[2] = w.wv;
         g.rows[0] = qdim; g.rows[1] = kvdim; g.rows[2] = kvdim; g.total_rows = qkv_dim;
         g.out = qkv; g.out_stride = qkv_dim; g.ncols = ncols;
+        void* k_layer = c->k_cache + (size_t)l * c->kv_layer_bytes();
+        void* v_layer = c->v_cache + (size_t)l * c->kv_layer_bytes();
         if (mfma) {
             D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.attn_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
             g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
-            Timed t(c, D3_K_QKV, s);
-            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+            {
+                Timed t(c, D3_K_QKV, s);
+                D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+            }
+            RopeArgs r{};
+            r.qkv = qkv; r.k_cache = k_layer; r.v_cache = v_layer; r.rope_cs = rope_cs;
+            r.cm = cm; r.ncols = ncols; r.H = d.n_heads; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
+            D3_HIP(launch_rope_append(r, d.kv_dtype, s));
         } else {
+            // the GEMV epilogue rotates q and k and appends the new K/V row itself
             g.x = x; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
+            g.rope_cs = rope_cs; g.k_cache = k_layer; g.v_cache = v_layer; g.cm = cm;
+            g.H = d.n_heads; g.H_kv = d.n_kv_heads; g.hd = hd; g.max_seq = d.max_seq; g.kv_dtype = d.kv_dtype;
             Timed t(c, D3_K_QKV, s);
-            D3_HIP(alu(g, 0, ncols, MODE_STORE, true));
+            D3_HIP(alu(g, 0, ncols, MODE_QKV_ROPE, true));
         }
-        RopeArgs r{};
-        r.qkv = qkv;
-        r.k_cache = c->k_cache + (size_t)l * c->kv_layer_bytes();
-        r.v_cache = c->v_cache + (size_t)l * c->kv_layer_bytes();
-        r.inv_freq = c->at<double>(c->lay.inv_freq);
-        r.cm = cm; r.ncols = ncols; r.H = d.n_heads; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
-        D3_HIP(launch_rope_append(r, d.kv_dtype, s));
         AttnArgs at{};
-        at.q = qkv; at.q_stride = qkv_dim; at.k_cache = r.k_cache; at.v_cache = r.v_cache; at.cm = cm;
+        at.q = qkv; at.q_stride = qkv_dim; at.k_cache = k_layer; at.v_cache = v_layer; at.cm = cm;
         at.ncols = ncols; at.H = d.n_heads; at.H_kv = d.n_kv_heads; at.hd = hd; at.max_seq = d.max_seq;
         at.split_len = split_len; at.n_splits = n_splits;
-        at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml);
+        at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml); at.tickets = c->at<int>(c->lay.tickets);
         at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
         {
             Timed t(c, D3_K_ATTN, s);
@@ -357,6 +404,32 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     return D3_OK;
 }
 
+// The whole decode step as one cooperative launch (decode_mega.hip).
+int decode_persistent(d3_ctx* c, const int32_t* tok_in, int step_i, int32_t* tok_out, float* logits, float* hidden_dump, hipStream_t s) {
+    const d3_model_desc& d = c->desc;
+    MegaArgs m{};
+    m.d_model = d.d_model; m.H = d.n_heads; m.H_kv = d.n_kv_heads; m.d_ffn = d.d_ffn; m.vocab = d.vocab; m.max_seq = d.max_seq;
+    m.kv_dtype = d.kv_dtype; m.eps = d.rms_eps;
+    m.tok_emb = c->tok_emb; m.final_norm = static_cast<const float*>(c->final_norm); m.lm_head = c->lm_head;
+    m.layers = c->at<d3_layer_weights>(c->lay.layer_ptrs);
+    m.k_cache = c->k_cache; m.v_cache = c->v_cache; m.kv_layer_bytes = c->kv_layer_bytes();
+    m.inv_freq = c->at<double>(c->lay.inv_freq);
+    m.layer_ids = c->at<int32_t>(c->lay.layer_table) + (size_t)step_i * d.n_layers;
+    m.n_ids = c->keep[step_i];
+    m.pos = c->n_ctx;
+    m.tok_in = tok_in; m.tok_out = tok_out; m.logits = logits; m.hidden_dump = hidden_dump;
+    pick_splits(c, 1, c->n_ctx + 1, c->mega_wgs, &m.split_len, &m.n_splits);
+    m.x = c->at<float>(c->lay.x); m.qkv = c->at<float>(c->lay.qkv); m.attn_o = c->at<float>(c->lay.attn_o); m.act = c->at<float>(c->lay.act);
+    m.part_o = c->at<float>(c->lay.part_o); m.part_ml = c->at<float>(c->lay.part_ml);
+    m.cand_val = c->at<float>(c->lay.cand_val); m.cand_idx = c->at<int>(c->lay.cand_idx);
+    m.tickets = c->at<int>(c->lay.tickets); m.rope_cs = c->at<float2>(c->lay.rope_cs);
+    m.barrier_state = c->at<unsigned>(c->lay.barrier); m.barrier_epoch = c->bar_epoch; m.max_spins = 1 << 21;
+    Timed t(c, D3_K_STEP, s);
+    D3_HIP(launch_decode_mega(m, d.kv_dtype, c->mega_wgs, s));
+    c->bar_epoch += 5u * (unsigned)m.n_ids + 2u;     // the launch passes exactly this many barriers
+    return D3_OK;
+}
+
 }  // namespace
 
 extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32_t pos_begin, int32_t* next_tok,
@@ -404,10 +477,16 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     if (ctx->n_ctx >= ctx->desc.max_seq) return fail(D3_ERANGE, "d3_decode_step: cache is full (%d rows)", ctx->n_ctx);
     const int L = ctx->desc.n_layers, B = ctx->B;
     const int kept = ctx->keep[step_i];
-    ColMap cm{0, B, 1, ctx->n_ctx};
-    HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
-    int rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
+    int rc;
+    if (ctx->mega_ok && B == 1) {
+        rc = decode_persistent(ctx, tok_in, step_i, tok_out, logits ? logits : ctx->at<float>(ctx->lay.logits), hidden_dump,
+                               static_cast<hipStream_t>(hip_stream));
+    } else {
+        ColMap cm{0, B, 1, ctx->n_ctx};
+        HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
+        rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
                      static_cast<hipStream_t>(hip_stream));
+    }
     if (rc != D3_OK) return rc;
     ctx->row_drop_begin[ctx->n_ctx] = ctx->drop_begin[step_i];
     ctx->row_n_drop[ctx->n_ctx] = L - kept;
@@ -453,7 +532,7 @@ extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
 
 extern "C" int d3_profile_select(d3_ctx* ctx, int32_t kernel_class) {
     if (!ctx) return fail(D3_EINVAL, "d3_profile_select: ctx is NULL");
-    if (kernel_class < D3_K_NONE || kernel_class > D3_K_LM_HEAD) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
+    if (kernel_class < D3_K_NONE || kernel_class > D3_K_STEP) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
     if (kernel_class != D3_K_NONE && ctx->prof_events.empty()) {
         ctx->prof_events.reserve(kMaxProfEvents);
         for (size_t i = 0; i < kMaxProfEvents; ++i) {
@@ -481,3 +560,18 @@ extern "C" int d3_profile_read(d3_ctx* ctx, double* total_ms, int64_t* launches)
     ctx->prof_used = 0;
     return D3_OK;
 }
+
+extern "C" int d3_sync_check(d3_ctx* ctx, void* hip_stream) {
+    if (!ctx) return fail(D3_EINVAL, "d3_sync_check: ctx is NULL");
+    D3_HIP(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+    unsigned abort_flag = 0;
+    D3_HIP(hipMemcpy(&abort_flag, ctx->at<unsigned>(ctx->lay.barrier) + 288, sizeof(unsigned), hipMemcpyDeviceToHost));
+    if (abort_flag != 0) {
+        D3_HIP(hipMemset(ctx->at<unsigned>(ctx->lay.barrier), 0, 512 * 4));
+        ctx->bar_epoch = 0;
+        return fail(D3_EDEVICE, "d3_sync_check: a persistent decode step gave up waiting at a grid barrier; its outputs are invalid");
+    }
+    return D3_OK;
+}
+
+extern "C" int d3_uses_persistent_step(const d3_ctx* ctx) { return ctx && ctx->mega_ok ? ctx->mega_wgs : 0; }

@@ -43,6 +43,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Data handed from one workgroup to another inside a kernel is written and read with agent-scope
+// accesses (coherent across the chip's eight L2s) instead of cache-wide fences, which cost tens of
+// microseconds here.  Protocol: producer st_agent(...), wait_stores(), workgroup barrier, then one
+// thread bumps an arrival counter; the consumer sees the counter and reads with ld_agent(...).
+__device__ __forceinline__ void st_agent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_agent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -55,7 +63,7 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---------------- projections ----------------
-enum GemvMode { MODE_STORE = 0, MODE_RESID = 1, MODE_SWIGLU = 2 };
+enum GemvMode { MODE_STORE = 0, MODE_RESID = 1, MODE_SWIGLU = 2, MODE_QKV_ROPE = 3 };
 
 struct GemvArgs {
     // activations: fp32 [ncols][x_stride] (ALU path) or bf16 hi/lo halves [.][x_stride] (MFMA path)
@@ -75,6 +83,13 @@ struct GemvArgs {
     bf16_t* out_lo;
     int out_stride;
     int ncols;
+    // MODE_QKV_ROPE only: rotate q and k, append k and v to this block's cache
+    const float2* rope_cs;   // [columns of the pass][hd/2] (cos, sin) of pos * base^(-2j/hd)
+    void* k_cache;           // this block's [max_batch][H_kv][max_seq][hd]
+    void* v_cache;
+    ColMap cm;
+    int col0;                // pass column of this launch's column 0
+    int H, H_kv, hd, max_seq, kv_dtype;
 };
 
 // returns hipError_t as int
@@ -87,14 +102,15 @@ int launch_norm_split(const float* x, int x_stride, const float* gain, float eps
                       bf16_t* hi, bf16_t* lo, hipStream_t s);
 
 // ---------------- the rest of a block ----------------
+// x[c][:] = E[token(c)][:], and the pass's rotary table rope_cs[c][j] = (cos, sin)(pos(c) * inv_freq[j])
 int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
-                 int vocab, float* x, hipStream_t s);
+                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, hipStream_t s);
 
 struct RopeArgs {
     float* qkv;            // [ncols][(H + 2 H_kv) * hd] fp32: q rotated in place
     void* k_cache;         // this block's [max_batch][H_kv][max_seq][hd]
     void* v_cache;
-    const double* inv_freq;  // [hd/2]
+    const float2* rope_cs;   // [ncols][hd/2] (cos, sin) of this pass
     ColMap cm;
     int ncols, H, H_kv, hd, max_seq;
 };
@@ -110,6 +126,7 @@ struct AttnArgs {
     int split_len, n_splits;
     float* part_o;         // [ncols][H][n_splits][hd]
     float* part_ml;        // [ncols][H][n_splits][2]  (max, sum)
+    int* tickets;          // [ncols][H] arrival counters, zero between launches
     float* out;            // [ncols][H*hd]
     bf16_t* out_hi;        // optional split copy
     bf16_t* out_lo;

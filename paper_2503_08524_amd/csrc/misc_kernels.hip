@@ -9,8 +9,15 @@ namespace {
 // ---------------- embedding gather: x[c][:] = E[token(c)][:] ----------------
 template <typename W>
 __global__ __launch_bounds__(256) void embed_kernel(const W* __restrict__ emb, const int32_t* __restrict__ tokens,
-                                                    ColMap cm, int d, int vocab, float* __restrict__ x) {
+                                                    ColMap cm, int d, int vocab, float* __restrict__ x,
+                                                    const double* __restrict__ inv_freq, int half_hd,
+                                                    float2* __restrict__ rope_cs) {
     const int c = blockIdx.x;
+    if ((int)threadIdx.x < half_hd) {       // the rotation angles depend on the position only, not on the block
+        double sn, cs;
+        sincos((double)cm.pos(c) * inv_freq[threadIdx.x], &sn, &cs);
+        rope_cs[(size_t)c * half_hd + threadIdx.x] = make_float2((float)cs, (float)sn);
+    }
     int tok = tokens[cm.tok_index(c)];
     tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);   // stay inside the table whatever the caller fed
     const W* row = emb + (size_t)tok * d;
@@ -62,11 +69,10 @@ __global__ __launch_bounds__(64) void rope_append_kernel(RopeArgs a) {
     const int seq = a.cm.seq(c), pos = a.cm.pos(c);
     float* row = a.qkv + (size_t)c * (a.H + 2 * a.H_kv) * a.hd + (size_t)head * a.hd;
     if (head < a.H + a.H_kv) {
-        double sn, cs;
-        sincos((double)pos * a.inv_freq[j], &sn, &cs);
+        const float2 cs = a.rope_cs[(size_t)c * half + j];
         const float x0 = row[j], x1 = row[j + half];
-        const float y0 = x0 * (float)cs - x1 * (float)sn;
-        const float y1 = x0 * (float)sn + x1 * (float)cs;
+        const float y0 = x0 * cs.x - x1 * cs.y;
+        const float y1 = x0 * cs.y + x1 * cs.x;
         if (head < a.H) {
             row[j] = y0;
             row[j + half] = y1;
@@ -136,11 +142,13 @@ __global__ __launch_bounds__(64) void fill_kernel(FillArgs a, int bytes_per_vec)
 }  // namespace
 
 int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
-                 int vocab, float* x, hipStream_t s) {
+                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, hipStream_t s) {
     if (weight_dtype == 0)
-        hipLaunchKernelGGL(embed_kernel<float>, dim3(ncols), dim3(256), 0, s, static_cast<const float*>(tok_emb), tokens, cm, d, vocab, x);
+        hipLaunchKernelGGL(embed_kernel<float>, dim3(ncols), dim3(256), 0, s, static_cast<const float*>(tok_emb), tokens, cm, d, vocab, x,
+                           inv_freq, half_hd, rope_cs);
     else
-        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(ncols), dim3(256), 0, s, static_cast<const bf16_t*>(tok_emb), tokens, cm, d, vocab, x);
+        hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(ncols), dim3(256), 0, s, static_cast<const bf16_t*>(tok_emb), tokens, cm, d, vocab, x,
+                           inv_freq, half_hd, rope_cs);
     return (int)hipGetLastError();
 }
 

@@ -59,6 +59,18 @@ def test_small_gqa(B, kv):
     _run(SMALL_GQA, B, 37, 6, 0.8, 1, forced_seed=8, kv_dtype=kv)
 
 
+@pytest.mark.parametrize("persistent", [True, False])
+@pytest.mark.parametrize("kv", ["f16", "bf16", "f32"])
+def test_batch1_decode_as_one_persistent_launch_and_as_separate_launches(persistent, kv):
+    # head_dim 128, bf16 weights, batch 1: the whole step is one cooperative launch unless switched off
+    _run(SMALL_GQA, 1, 70, 12, 0.85, 1, forced_seed=14, kv_dtype=kv, persistent=persistent)
+
+
+def test_persistent_step_with_zero_blocks_and_free_running_tokens():
+    gpu, gens = _run(SMALL_GQA, 1, 9, 6, 0.5, 1, persistent=True)      # keep = 3, 1, 0, 0, ...: steps with no block at all
+    assert gens[0].keep[2] == 0
+
+
 def test_long_context_spans_several_attention_splits():
     _run(SMALL_BF16, 2, 700, 4, 0.9, 2, forced_seed=9)
 
@@ -72,8 +84,9 @@ def test_zero_blocks_kept():
     _run(SMALL_BF16, 1, 4, 5, 0.5, 1, forced_seed=11)
 
 
-def test_llama7b_widths_two_blocks_batch1():
-    _run(d3_inputs.LLAMA_7B.truncated(2), 1, 8, 5, 0.7, 1, forced_seed=12)
+@pytest.mark.parametrize("persistent", [True, False])
+def test_llama7b_widths_two_blocks_batch1(persistent):
+    _run(d3_inputs.LLAMA_7B.truncated(2), 1, 8, 5, 0.7, 1, forced_seed=12, persistent=persistent)
 
 
 def test_llama7b_widths_two_blocks_batch4():

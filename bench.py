@@ -73,7 +73,7 @@ def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill=True):
             if fill:
                 dec.fill_missing_kv(P + i - 1, P + i)
             cur, nxt = nxt, cur
-    torch.cuda.synchronize()
+    dec.sync_check()
     return time.perf_counter() - t0
 
 
@@ -154,18 +154,24 @@ def main() -> int:
             r["ideal_layer_count_ratio"] = shape.L / r["avg_blocks"]
             r["ideal_byte_ratio"] = results[1.0]["algorithmic_GB_per_token_step"] / r["algorithmic_GB_per_token_step"]
 
-    # dominant kernel: the fused RMSNorm + gate/up + SiLU*mul projection (45 % of a block's weight bytes),
-    # every launch bracketed by HIP events on the launch stream, over one more full-depth request
-    dec.profile_select(binding.D3_K_GATE_UP)
+    # dominant kernel, every launch bracketed by HIP events on the launch stream, over one more full-depth request
+    wbytes = 4 if shape.dtype == "f32" else 2
+    if dec.persistent_workgroups > 0:
+        # the persistent decode step: one launch = one token; its algorithmic bytes are the step's
+        keep1, _, _ = binding.d3_plan_depth(shape.L, 1.0, start, 0, G)
+        kernel = "persistent decode step (all %d blocks + lm_head + argmax in one launch)" % shape.L
+        kclass, bytes_per_launch = binding.D3_K_STEP, algorithmic_bytes(shape, B, P, G, keep1, kv_bytes) / (G - 1)
+    else:
+        kernel = "fused RMSNorm + gate/up + SiLU*mul projection"
+        kclass, bytes_per_launch = binding.D3_K_GATE_UP, 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4
+    dec.profile_select(kclass)
     run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, False)
     ms, n = dec.profile_read()
     dec.profile_select(binding.D3_K_NONE)
-    wbytes = 4 if shape.dtype == "f32" else 2
-    gate_up_bytes = 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4
-    achieved = gate_up_bytes / (ms / n * 1e-3) / 1e9 if n else 0.0
-    roofline = {"bound": "hbm", "kernel": "fused RMSNorm + gate/up + SiLU*mul projection", "achieved": achieved,
+    achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9 if n else 0.0
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": gate_up_bytes}
+                "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": bytes_per_launch}
 
     out = {
         "metric": "decode tokens/sec (D^3, alpha=%g) at the Llama-7B shape; achieved HBM GB/s beside it" % alphas[0]
@@ -176,6 +182,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{shape.name} B={B} P={P} G={G} alpha={alphas[0]} start_layer={start}",
                    "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
+                   "persistent_step_workgroups": dec.persistent_workgroups,
                    "fill_every_step": not args.no_fill},
         "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
         "by_alpha": {str(a): r for a, r in results.items()},

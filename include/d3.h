@@ -156,16 +156,22 @@ typedef enum {
 int d3_profile_select(d3_ctx *ctx, int32_t kernel_class);
 int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
 
-/* Batch-1 decode steps of bf16 models with head_dim 128 run as ONE persistent cooperative
+/* With the environment variable D3_PERSISTENT=1 at d3_create, batch-1 decode steps of bf16 models
+ * with head_dim 128 run as ONE persistent cooperative
  * launch per step whose phases are separated by software grid barriers (Section 3.4: the step's
  * cost is the kept blocks' weights, so launch overheads between projections are what is left to
  * remove).  Every barrier wait is bounded; if one ever expires the step's outputs are invalid.
  * d3_sync_check synchronises the stream and reports that case as D3_EDEVICE (and re-arms the
  * barrier); D3_OK otherwise.  d3_uses_persistent_step returns the launch's workgroup count, or 0
- * when the context decodes with one launch per projection (other shapes, batch > 1, or the
- * environment variable D3_PERSISTENT=0 at d3_create). */
+ * when the context decodes with one launch per projection (the default). */
 int d3_sync_check(d3_ctx *ctx, void *hip_stream);
 int d3_uses_persistent_step(const d3_ctx *ctx);
+
+/* Debug aid for the persistent step: device_buffer (dev, uint64 [workgroups][14 * n_layers], or NULL to
+ * switch off) receives every workgroup's 100 MHz timestamps at the phase boundaries of the next steps:
+ * per kept block 14 marks (start / staged / done of the QKV projection, attention start / done, then
+ * start / staged / done of the O, gate-up and down projections). */
+int d3_debug_timeline(d3_ctx *ctx, void *device_buffer);
 
 #ifdef __cplusplus
 }

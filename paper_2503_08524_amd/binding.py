@@ -65,6 +65,7 @@ def load_library() -> C.CDLL:
         lib.d3_truncate.argtypes = [vp, i32]
         lib.d3_sync_check.argtypes = [vp, vp]
         lib.d3_uses_persistent_step.argtypes = [vp]
+        lib.d3_debug_timeline.argtypes = [vp, vp]
         lib.d3_profile_select.argtypes = [vp, i32]
         lib.d3_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _LIB = lib
@@ -178,6 +179,9 @@ class Decoder:
     @property
     def persistent_workgroups(self) -> int:
         return int(self.lib.d3_uses_persistent_step(self.ctx))
+
+    def debug_timeline(self, buf) -> None:
+        _check(self.lib.d3_debug_timeline(self.ctx, _ptr(buf)))
 
     def truncate(self, n_rows: int) -> None:
         _check(self.lib.d3_truncate(self.ctx, n_rows))

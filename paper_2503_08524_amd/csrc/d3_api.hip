@@ -109,7 +109,9 @@ struct d3_ctx {
     // persistent one-launch decode step (batch 1, bf16 weights, head_dim 128)
     bool mega_ok;
     int mega_wgs;                 // workgroups of the cooperative launch
+    int mega_depth;               // weight-load steps in flight per wave (D3_PERSISTENT_DEPTH: 8, 12, 16)
     unsigned bar_epoch;           // grid barriers completed so far
+    unsigned long long* debug_ts; // optional device buffer for the persistent step's phase timeline
     // per-launch timing of one kernel class
     int prof_class;
     std::vector<hipEvent_t> prof_events;   // pairs (start, stop), created on first use
@@ -179,16 +181,18 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->row_n_drop.assign(desc->max_seq, 0);
 
     // persistent decode step: needs the block pointer table and zeroed barrier words on the device
-    c->mega_ok = false; c->mega_wgs = 0; c->bar_epoch = 0;
+    c->mega_ok = false; c->mega_wgs = 0; c->bar_epoch = 0; c->debug_ts = nullptr;
     {
         const char* env = getenv("D3_PERSISTENT");
-        const bool want = !(env && atoi(env) == 0);
+        const bool want = env && atoi(env) != 0;        // opt-in until it beats one launch per projection
         int per_cu = 1;
+        c->mega_depth = 8;
+        if (const char* e3 = getenv("D3_PERSISTENT_DEPTH")) { const int v = atoi(e3); if (v == 8 || v == 12 || v == 16) c->mega_depth = v; }
         if (const char* e2 = getenv("D3_PERSISTENT_WGS_PER_CU")) { const int v = atoi(e2); if (v >= 1 && v <= 4) per_cu = v; }
         if (want && desc->weight_dtype == D3_BF16 && desc->head_dim == 128 && c->alu_ok) {
             MegaArgs probe{};
             probe.d_model = desc->d_model; probe.H = desc->n_heads; probe.d_ffn = desc->d_ffn; probe.split_len = 8192;
-            const int fit = mega_max_workgroups(desc->kv_dtype, mega_lds_bytes(probe), c->n_cu);
+            const int fit = mega_max_workgroups(desc->kv_dtype, c->mega_depth, mega_lds_bytes(probe), c->n_cu);
             int wgs = c->n_cu * per_cu;
             if (wgs > fit) wgs = fit;
             const long long waves = (long long)wgs * 4;
@@ -424,8 +428,9 @@ int decode_persistent(d3_ctx* c, const int32_t* tok_in, int step_i, int32_t* tok
     m.cand_val = c->at<float>(c->lay.cand_val); m.cand_idx = c->at<int>(c->lay.cand_idx);
     m.tickets = c->at<int>(c->lay.tickets); m.rope_cs = c->at<float2>(c->lay.rope_cs);
     m.barrier_state = c->at<unsigned>(c->lay.barrier); m.barrier_epoch = c->bar_epoch; m.max_spins = 1 << 21;
+    m.debug_ts = c->debug_ts; m.debug_stride = 14 * d.n_layers;
     Timed t(c, D3_K_STEP, s);
-    D3_HIP(launch_decode_mega(m, d.kv_dtype, c->mega_wgs, s));
+    D3_HIP(launch_decode_mega(m, d.kv_dtype, c->mega_depth, c->mega_wgs, s));
     c->bar_epoch += 5u * (unsigned)m.n_ids + 2u;     // the launch passes exactly this many barriers
     return D3_OK;
 }
@@ -575,3 +580,9 @@ extern "C" int d3_sync_check(d3_ctx* ctx, void* hip_stream) {
 }
 
 extern "C" int d3_uses_persistent_step(const d3_ctx* ctx) { return ctx && ctx->mega_ok ? ctx->mega_wgs : 0; }
+
+extern "C" int d3_debug_timeline(d3_ctx* ctx, void* device_buffer) {
+    if (!ctx) return fail(D3_EINVAL, "d3_debug_timeline: ctx is NULL");
+    ctx->debug_ts = static_cast<unsigned long long*>(device_buffer);
+    return D3_OK;
+}

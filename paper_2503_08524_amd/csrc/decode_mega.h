@@ -34,10 +34,12 @@ struct MegaArgs {
     unsigned* barrier_state;          // 512 words, zero before the first launch
     unsigned barrier_epoch;           // barriers completed by earlier launches
     int max_spins;
+    unsigned long long* debug_ts;     // optional: every workgroup's 100 MHz timestamps at phase boundaries (14 per block)
+    int debug_stride;                 // marks per workgroup row
 };
 
 size_t mega_lds_bytes(const MegaArgs& m);
-int mega_max_workgroups(int kv_dtype, size_t lds_bytes, int n_cu);      // co-resident workgroups, 0 on error
-int launch_decode_mega(const MegaArgs& m, int kv_dtype, int n_wg, hipStream_t s);   // hipError_t as int
+int mega_max_workgroups(int kv_dtype, int depth, size_t lds_bytes, int n_cu);      // co-resident workgroups, 0 on error
+int launch_decode_mega(const MegaArgs& m, int kv_dtype, int depth, int n_wg, hipStream_t s);   // hipError_t as int
 
 }  // namespace d3

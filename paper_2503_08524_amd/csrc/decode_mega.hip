@@ -22,8 +22,6 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
-constexpr int kD = kGemvDepth;
-typedef GemvPipe<bf16_t, kD> Pipe;
 
 __device__ __forceinline__ unsigned ld_agent_u(const unsigned* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
@@ -64,19 +62,30 @@ __device__ __forceinline__ bool grid_barrier(Barrier& b) {
     return !b.dead;
 }
 
-template <int MODE, bool NORM>
-__device__ __forceinline__ void gemv_phase(const GemvArgs& a, float4* xs, float (*red)[kWaves], GemvEpBuf<1>& ep, Pipe& pipe,
-                                           int gw, int nw, float* dump) {
+struct Stamps {            // debug timeline, one row of `stride` marks per workgroup
+    unsigned long long* ts;
+    int n, stride;
+    __device__ __forceinline__ void mark() {
+        if (ts && threadIdx.x == 0 && n < stride) ts[(size_t)blockIdx.x * stride + n] = wall_clock64();
+        n += 1;
+    }
+};
+
+template <int MODE, bool NORM, int kD>
+__device__ __forceinline__ void gemv_phase(const GemvArgs& a, float4* xs, float (*red)[kWaves], GemvEpBuf<1>& ep, GemvPipe<bf16_t, kD>& pipe,
+                                           int gw, int nw, Stamps& st) {
     float ss[1];
     gemv_stage_load<bf16_t, 1, NORM, true, kThreads>(a, xs, ss);
     gemv_stage_norm<bf16_t, 1, NORM, kThreads>(a, xs, ss, red);
-    (void)dump;
     __syncthreads();
+    st.mark();
     gemv_run<bf16_t, 1, MODE, kD, true>(a, xs, gw, nw, pipe, ep);
+    st.mark();
 }
 
-template <typename T>
+template <typename T, int kD>
 __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
+    typedef GemvPipe<bf16_t, kD> Pipe;
     extern __shared__ float4 lds[];                     // activations of the current projection / attention scores
     __shared__ float red[1][kWaves];
     __shared__ GemvEpBuf<1> ep[kWaves];
@@ -96,6 +105,7 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
 
     const ColMap cm{0, 1, 1, m.pos};
     Pipe pipe;
+    Stamps st{m.debug_ts, 0, m.debug_stride};
 
     // ---- first projection's weights start streaming, then the embedding and the rotary table ----
     GemvArgs qkv{};
@@ -145,7 +155,8 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
         const d3_layer_weights& w = m.layers[l];
 
         // A: RMSNorm + QKV + rotary embedding + cache append
-        gemv_phase<MODE_QKV_ROPE, true>(qkv, lds, red, ep[wave], pipe, gw, nw, nullptr);
+        st.mark();
+        gemv_phase<MODE_QKV_ROPE, true, kD>(qkv, lds, red, ep[wave], pipe, gw, nw, st);
         wait_stores();                      // q, k, v are out before the next loads queue up behind them
 
         // the O-projection's first rows stream while attention runs
@@ -156,15 +167,18 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
 
         // B: attention over the cache (the newest row comes from the projection buffer)
         at.k_cache = qkv.k_cache; at.v_cache = qkv.v_cache;
+        st.mark();
         for (int item = wg; item < m.H * m.n_splits; item += n_wg) {
             attn_split<T, HD, true>(at, item % m.n_splits, item / m.n_splits, 0, reinterpret_cast<float*>(lds), ash);
             __syncthreads();
         }
         wait_stores();
+        st.mark();
         if (!grid_barrier(bar)) return;
 
         // C: x += Wo . attention
-        gemv_phase<MODE_RESID, false>(o, lds, red, ep[wave], pipe, gw, nw, nullptr);
+        st.mark();
+        gemv_phase<MODE_RESID, false, kD>(o, lds, red, ep[wave], pipe, gw, nw, st);
         wait_stores();
         GemvArgs u{};
         u.x = m.x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.eps = m.eps; u.K = dm;
@@ -173,7 +187,8 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
         if (!grid_barrier(bar)) return;
 
         // D: RMSNorm + gate/up + SiLU(gate) * up
-        gemv_phase<MODE_SWIGLU, true>(u, lds, red, ep[wave], pipe, gw, nw, nullptr);
+        st.mark();
+        gemv_phase<MODE_SWIGLU, true, kD>(u, lds, red, ep[wave], pipe, gw, nw, st);
         wait_stores();
         GemvArgs dn{};
         dn.x = m.act; dn.x_stride = F; dn.K = F; dn.w[0] = w.w_down; dn.rows[0] = dm; dn.total_rows = dm; dn.out = m.x; dn.out_stride = dm; dn.ncols = 1;
@@ -181,7 +196,8 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
         if (!grid_barrier(bar)) return;
 
         // E: x += Wd . act
-        gemv_phase<MODE_RESID, false>(dn, lds, red, ep[wave], pipe, gw, nw, nullptr);
+        st.mark();
+        gemv_phase<MODE_RESID, false, kD>(dn, lds, red, ep[wave], pipe, gw, nw, st);
         wait_stores();
         if (e + 1 < m.n_ids) { make_qkv(m.layer_ids[e + 1]); gemv_preload<bf16_t, MODE_QKV_ROPE, kD>(qkv, gw, nw, pipe); }
         else gemv_preload<bf16_t, MODE_STORE, kD>(head, gw, nw, pipe);
@@ -255,24 +271,28 @@ size_t mega_lds_bytes(const MegaArgs& m) {
     return xs > sc ? xs : sc;
 }
 
-int mega_max_workgroups(int kv_dtype, size_t lds_bytes, int n_cu) {
+namespace {
+const void* mega_kernel(int kv_dtype, int depth) {
+#define D3_PICK(T) (depth >= 16 ? (const void*)decode_mega_kernel<T, 16> : depth >= 12 ? (const void*)decode_mega_kernel<T, 12> : (const void*)decode_mega_kernel<T, 8>)
+    return kv_dtype == 0 ? D3_PICK(float) : kv_dtype == 1 ? D3_PICK(bf16_t) : D3_PICK(f16_t);
+#undef D3_PICK
+}
+}  // namespace
+
+int mega_max_workgroups(int kv_dtype, int depth, size_t lds_bytes, int n_cu) {
     int per_cu = 0;
-    const void* f = kv_dtype == 0 ? (const void*)decode_mega_kernel<float>
-                  : kv_dtype == 1 ? (const void*)decode_mega_kernel<bf16_t> : (const void*)decode_mega_kernel<f16_t>;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, f, kThreads, lds_bytes) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, mega_kernel(kv_dtype, depth), kThreads, lds_bytes) != hipSuccess) return 0;
     return per_cu * n_cu;
 }
 
 // Requirements (checked by the caller): bf16 weights, head_dim 128, batch 1, a wave parks at most
 // kGemvEpCap units per projection, n_wg <= mega_max_workgroups (the launch is cooperative, so the
-// runtime refuses a grid that cannot be co-resident).
-int launch_decode_mega(const MegaArgs& m, int kv_dtype, int n_wg, hipStream_t s) {
+// runtime refuses a grid that cannot be co-resident).  depth: weight-load steps in flight per wave (8, 12 or 16).
+int launch_decode_mega(const MegaArgs& m, int kv_dtype, int depth, int n_wg, hipStream_t s) {
     const size_t lds = mega_lds_bytes(m);
     MegaArgs copy = m;
     void* args[] = {&copy};
-    const void* f = kv_dtype == 0 ? (const void*)decode_mega_kernel<float>
-                  : kv_dtype == 1 ? (const void*)decode_mega_kernel<bf16_t> : (const void*)decode_mega_kernel<f16_t>;
-    return (int)hipLaunchCooperativeKernel(f, dim3(n_wg), dim3(kThreads), args, (unsigned)lds, s);
+    return (int)hipLaunchCooperativeKernel(mega_kernel(kv_dtype, depth), dim3(n_wg), dim3(kThreads), args, (unsigned)lds, s);
 }
 
 }  // namespace d3

@@ -167,10 +167,10 @@ int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
 int d3_sync_check(d3_ctx *ctx, void *hip_stream);
 int d3_uses_persistent_step(const d3_ctx *ctx);
 
-/* Debug aid for the persistent step: device_buffer (dev, uint64 [workgroups][14 * n_layers], or NULL to
+/* Debug aid for the persistent step: device_buffer (dev, uint64 [workgroups][10 * n_layers], or NULL to
  * switch off) receives every workgroup's 100 MHz timestamps at the phase boundaries of the next steps:
- * per kept block 14 marks (start / staged / done of the QKV projection, attention start / done, then
- * start / staged / done of the O, gate-up and down projections). */
+ * per kept block 10 marks (start / done of the QKV projection, of attention, and of the O, gate-up and
+ * down projections). */
 int d3_debug_timeline(d3_ctx *ctx, void *device_buffer);
 
 #ifdef __cplusplus

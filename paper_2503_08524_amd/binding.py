@@ -39,7 +39,7 @@ class _Weights(C.Structure):
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "libd3.so")
+    return os.environ.get("D3_LIBRARY", os.path.join(_HERE, "libd3.so"))
 
 
 def load_library() -> C.CDLL:

@@ -33,7 +33,9 @@ def is_stale() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return LIB
-    cmd = [HIPCC] + FLAGS + ["-x", "hip"] + sources() + ["-o", LIB]
+    extra = os.environ.get("D3_BUILD_DEFINES", "").split()          # e.g. "-DD3_GEMV_DEPTH=4" for tuning experiments
+    out_path = os.environ.get("D3_BUILD_OUT", LIB)
+    cmd = [HIPCC] + FLAGS + extra + ["-x", "hip"] + sources() + ["-o", out_path]
     res = subprocess.run(cmd, capture_output=True, text=True)
     out = "\n".join(ln for ln in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in ln)
     if res.returncode != 0:

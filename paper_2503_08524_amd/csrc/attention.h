@@ -1,5 +1,5 @@
 // Device-side body of the decode attention (see attention.hip): one (column, head, context split)
-// per call by a 256-thread workgroup, plus the merge of the splits by whichever split arrives last.
+// per call by a workgroup of NW waves, plus the merge of the splits by whichever split arrives last.
 #pragma once
 #include "d3_common.h"
 
@@ -32,10 +32,10 @@ template <> struct KvVec<f16_t> {
     static __device__ __forceinline__ float round(float v) { return (float)(f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
 };
 
-template <int HD>
+template <int HD, int NW>
 struct AttnShared {
-    float red_m[4], red_s[4];
-    float osum[4][HD];
+    float red_m[NW], red_s[NW];
+    float osum[NW][HD];
     int is_last;
 };
 
@@ -43,12 +43,12 @@ struct AttnShared {
 // q and that row are read from the fp32 projection buffer with agent-scope loads (the row rounded
 // to the cache's element type, i.e. exactly what later steps will read back), and the merged
 // output is published with agent-scope stores.
-template <typename T, int HD, bool FUSED>
-__device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, int c, float* sc, AttnShared<HD>& sh) {
+template <typename T, int HD, bool FUSED, int NW>
+__device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, int c, float* sc, AttnShared<HD, NW>& sh) {
     constexpr int EPL = KvVec<T>::N;       // elements per lane per 16-byte load
     constexpr int LPR = HD / EPL;          // lanes that share one cache row
     constexpr int RPW = 64 / LPR;          // rows per wave per load
-    constexpr int RPB = RPW * 4;           // rows per workgroup per load
+    constexpr int RPB = RPW * NW;          // rows per workgroup per load
     constexpr int U = 4;                   // loads in flight per lane
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -76,20 +76,83 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
         for (int e = 0; e < EPL; ++e) qv[e] = (FUSED ? ld_agent(qp + e) : qp[e]) * scale;
     }
 
-    // ---- scores ----
     const int iters = (n + RPB - 1) / RPB;
+    constexpr int ITMAX = 8;               // a split of up to ITMAX * RPB rows keeps all its K and V rows in registers
+    float acc[EPL];
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
+    float m, lsum = 0.f;
+    if (iters <= ITMAX) {
+        // short split: K and V loads all go out together (V does not wait for the softmax)
+        uint4 kv[ITMAX], vv[ITMAX];
+#pragma unroll
+        for (int u = 0; u < ITMAX; ++u) {
+            const int j = j0 + (u * NW + wave) * RPW + rg;
+            const int jc = j < j1 ? j : j1 - 1;
+            if (u < iters) {
+                kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
+                vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
+            }
+        }
+        float sv[ITMAX];
+        float lmax = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < ITMAX; ++u) {
+            sv[u] = -INFINITY;
+            if (u < iters) {
+                const int j = j0 + (u * NW + wave) * RPW + rg;
+                float kf[EPL];
+                KvVec<T>::unpack(kv[u], kf);
+                if (FUSED && j == ctx - 1) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
+                }
+                float s = 0.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
+#pragma unroll
+                for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+                if (j < j1) { sv[u] = s; lmax = fmaxf(lmax, s); }
+            }
+        }
+        lmax = wave_max(lmax);
+        if (lane == 0) sh.red_m[wave] = lmax;
+        __syncthreads();
+        m = sh.red_m[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) m = fmaxf(m, sh.red_m[w]);
+#pragma unroll
+        for (int u = 0; u < ITMAX; ++u) {
+            if (u < iters) {
+                const int j = j0 + (u * NW + wave) * RPW + rg;
+                const float p = expf(sv[u] - m);                    // exp(-inf) = 0 for rows past the split
+                if (sub == 0) lsum += p;
+                float vf[EPL];
+                KvVec<T>::unpack(vv[u], vf);
+                if (FUSED && j == ctx - 1) {
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
+                }
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+            }
+        }
+        lsum = wave_sum(lsum);
+        if (lane == 0) sh.red_s[wave] = lsum;
+    } else {
+    // ---- scores ----
     float lmax = -INFINITY;
     for (int it = 0; it < iters; it += U) {
         uint4 kv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
             const int jc = j < j1 ? j : j1 - 1;
             kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
             float kf[EPL];
             KvVec<T>::unpack(kv[u], kf);
             if (FUSED && j == ctx - 1) {
@@ -110,11 +173,12 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
     lmax = wave_max(lmax);
     if (lane == 0) sh.red_m[wave] = lmax;
     __syncthreads();
-    const float m = fmaxf(fmaxf(sh.red_m[0], sh.red_m[1]), fmaxf(sh.red_m[2], sh.red_m[3]));
+    m = sh.red_m[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) m = fmaxf(m, sh.red_m[w]);
 
     // ---- probabilities (relative to this split's max) ----
-    float lsum = 0.f;
-    for (int t = tid; t < n; t += 256) {
+    for (int t = tid; t < n; t += NW * 64) {
         const float p = expf(sc[t] - m);
         sc[t] = p;
         lsum += p;
@@ -124,20 +188,17 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
     __syncthreads();
 
     // ---- weighted sum of V rows ----
-    float acc[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
     for (int it = 0; it < iters; it += U) {
         uint4 vv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
             const int jc = j < j1 ? j : j1 - 1;
             vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * 4 + wave) * RPW + rg;
+            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
             const float p = j < j1 ? sc[j - j0] : 0.f;
             float vf[EPL];
             KvVec<T>::unpack(vv[u], vf);
@@ -149,6 +210,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
             for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
         }
     }
+    }
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
 #pragma unroll
@@ -159,10 +221,18 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
         for (int e = 0; e < EPL; ++e) sh.osum[wave][sub * EPL + e] = acc[e];
     }
     __syncthreads();
-    if (tid < HD) st_agent(&a.part_o[pidx * HD + tid], sh.osum[0][tid] + sh.osum[1][tid] + sh.osum[2][tid] + sh.osum[3][tid]);
+    if (tid < HD) {
+        float o = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) o += sh.osum[w][tid];
+        st_agent(&a.part_o[pidx * HD + tid], o);
+    }
     if (tid == 0) {
+        float l = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) l += sh.red_s[w];
         st_agent(&a.part_ml[pidx * 2], m);
-        st_agent(&a.part_ml[pidx * 2 + 1], sh.red_s[0] + sh.red_s[1] + sh.red_s[2] + sh.red_s[3]);
+        st_agent(&a.part_ml[pidx * 2 + 1], l);
     }
 
     // ---- the split that arrives last merges all splits of this (column, head) ----
@@ -176,14 +246,32 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
     __syncthreads();
     if (!sh.is_last) return;
     if (tid < HD) {
+        // all partials are fetched in rounds of 8 splits (one round trip each), merged with a running max
         const size_t p0 = ((size_t)c * a.H + h) * a.n_splits;
-        float gm = -INFINITY;
-        for (int s = 0; s < n_live; ++s) gm = fmaxf(gm, ld_agent(&a.part_ml[(p0 + s) * 2]));
-        float l = 0.f, o = 0.f;
-        for (int s = 0; s < n_live; ++s) {
-            const float w = expf(ld_agent(&a.part_ml[(p0 + s) * 2]) - gm);
-            l += ld_agent(&a.part_ml[(p0 + s) * 2 + 1]) * w;
-            o += ld_agent(&a.part_o[(p0 + s) * HD + tid]) * w;
+        float gm = -INFINITY, l = 0.f, o = 0.f;
+        for (int s0 = 0; s0 < n_live; s0 += 8) {
+            float ms[8], ls[8], os[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
+                ms[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
+                ls[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
+                os[k] = ld_agent(&a.part_o[(p0 + sidx) * HD + tid]);
+            }
+            float rm = gm;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[k]);
+            const float keep = expf(gm - rm);             // gm = -inf on the first round: exp(-inf) = 0
+            l *= keep; o *= keep;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (s0 + k < n_live) {
+                    const float w = expf(ms[k] - rm);
+                    l += ls[k] * w;
+                    o += os[k] * w;
+                }
+            }
+            gm = rm;
         }
         const float r = o / l;
         const size_t oi = (size_t)c * a.H * HD + (size_t)h * HD + tid;

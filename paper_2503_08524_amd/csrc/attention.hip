@@ -14,8 +14,8 @@ namespace {
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     extern __shared__ float sc[];          // scores, then probabilities, of this split
-    __shared__ AttnShared<HD> sh;
-    attn_split<T, HD, false>(a, blockIdx.x, blockIdx.y, blockIdx.z, sc, sh);
+    __shared__ AttnShared<HD, 4> sh;
+    attn_split<T, HD, false, 4>(a, blockIdx.x, blockIdx.y, blockIdx.z, sc, sh);
 }
 
 }  // namespace

@@ -95,6 +95,7 @@ struct d3_ctx {
     char *k_cache, *v_cache, *ws;
     Layout lay;
     int n_cu;
+    int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
     int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 2)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
@@ -109,7 +110,7 @@ struct d3_ctx {
     // persistent one-launch decode step (batch 1, bf16 weights, head_dim 128)
     bool mega_ok;
     int mega_wgs;                 // workgroups of the cooperative launch
-    int mega_depth;               // weight-load steps in flight per wave (D3_PERSISTENT_DEPTH: 8, 12, 16)
+    int mega_depth;               // weight-load steps in flight per wave (D3_PERSISTENT_DEPTH: 8 or 12)
     unsigned bar_epoch;           // grid barriers completed so far
     unsigned long long* debug_ts; // optional device buffer for the persistent step's phase timeline
     // per-launch timing of one kernel class
@@ -168,6 +169,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
     c->gemv_wgs_per_cu = 2;
+    c->gemv_head_start = 0;
+    if (const char* env = getenv("D3_GEMV_HEAD_START")) { const int v = atoi(env); if (v >= 0 && v <= 64) c->gemv_head_start = v; }
     if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {
         const int v = atoi(env);
         if (v >= 1 && v <= 8) c->gemv_wgs_per_cu = v;
@@ -187,7 +190,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
         const bool want = env && atoi(env) != 0;        // opt-in until it beats one launch per projection
         int per_cu = 1;
         c->mega_depth = 8;
-        if (const char* e3 = getenv("D3_PERSISTENT_DEPTH")) { const int v = atoi(e3); if (v == 8 || v == 12 || v == 16) c->mega_depth = v; }
+        if (const char* e3 = getenv("D3_PERSISTENT_DEPTH")) { const int v = atoi(e3); if (v == 8 || v == 12) c->mega_depth = v; }
         if (const char* e2 = getenv("D3_PERSISTENT_WGS_PER_CU")) { const int v = atoi(e2); if (v >= 1 && v <= 4) per_cu = v; }
         if (want && desc->weight_dtype == D3_BF16 && desc->head_dim == 128 && c->alu_ok) {
             MegaArgs probe{};
@@ -195,7 +198,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
             const int fit = mega_max_workgroups(desc->kv_dtype, c->mega_depth, mega_lds_bytes(probe), c->n_cu);
             int wgs = c->n_cu * per_cu;
             if (wgs > fit) wgs = fit;
-            const long long waves = (long long)wgs * 4;
+            const long long waves = (long long)wgs * 8;
             const long long most_units = desc->vocab / 2 > desc->d_ffn ? desc->vocab / 2 : desc->d_ffn;
             if (wgs >= 8 && waves * 64 >= most_units && waves <= 4096) { c->mega_ok = true; c->mega_wgs = wgs; }
         }
@@ -309,6 +312,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             h.out = g.out + (size_t)(first + c0) * g.out_stride;
             h.ncols = count - c0 < per ? count - c0 : per;
             h.col0 = first + c0;
+            h.head_start = c->gemv_head_start;
             int rc = launch_gemv_alu(h, d.weight_dtype, mode, norm, n_wg, s);
             if (rc != 0) return rc;
         }
@@ -381,8 +385,10 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s)); }
         } else {
             u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
+            if (e == n_ids - 1) u.debug_ts = c->debug_ts;      // debug timeline of the last block's gate/up launch
             { Timed t(c, D3_K_GATE_UP, s); D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true)); }
             dn.x = act; dn.x_stride = F;
+            if (e == n_ids - 1 && c->debug_ts) dn.debug_ts = c->debug_ts + 4096;
             { Timed t(c, D3_K_DOWN, s); D3_HIP(alu(dn, 0, ncols, MODE_RESID, false)); }
         }
         D3_HIP(dump(e + 1));
@@ -428,7 +434,7 @@ int decode_persistent(d3_ctx* c, const int32_t* tok_in, int step_i, int32_t* tok
     m.cand_val = c->at<float>(c->lay.cand_val); m.cand_idx = c->at<int>(c->lay.cand_idx);
     m.tickets = c->at<int>(c->lay.tickets); m.rope_cs = c->at<float2>(c->lay.rope_cs);
     m.barrier_state = c->at<unsigned>(c->lay.barrier); m.barrier_epoch = c->bar_epoch; m.max_spins = 1 << 21;
-    m.debug_ts = c->debug_ts; m.debug_stride = 14 * d.n_layers;
+    m.debug_ts = c->debug_ts; m.debug_stride = 10 * d.n_layers;
     Timed t(c, D3_K_STEP, s);
     D3_HIP(launch_decode_mega(m, d.kv_dtype, c->mega_depth, c->mega_wgs, s));
     c->bar_epoch += 5u * (unsigned)m.n_ids + 2u;     // the launch passes exactly this many barriers

@@ -90,6 +90,8 @@ struct GemvArgs {
     ColMap cm;
     int col0;                // pass column of this launch's column 0
     int H, H_kv, hd, max_seq, kv_dtype;
+    unsigned long long* debug_ts;   // optional: per-workgroup 100 MHz timestamps (entry, staged, done)
+    int head_start;                 // pause (units of 512 clocks) between issuing the activation loads and the weight preload
 };
 
 // returns hipError_t as int

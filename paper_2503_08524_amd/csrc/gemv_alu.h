@@ -10,10 +10,14 @@
 
 namespace d3 {
 
-constexpr int kGemvThreads = 256;
-constexpr int kGemvWaves = kGemvThreads / kWave;
+constexpr int kGemvWaves = 4;
+constexpr int kGemvThreads = kGemvWaves * kWave;
+constexpr int kGemvStageR = 12;             // float4 activation loads a thread issues ahead of the weights (K <= 12288 in one round)
 constexpr int kGemvLdsBudget = 60 * 1024;   // dynamic LDS per workgroup for the activations
-constexpr int kGemvDepth = 8;               // steps in flight per wave (16 KiB)
+#ifndef D3_GEMV_DEPTH
+#define D3_GEMV_DEPTH 4
+#endif
+constexpr int kGemvDepth = D3_GEMV_DEPTH;   // steps in flight per wave (2 KiB each)
 constexpr int kGemvEpCap = 64;              // finished units a wave can hold before writing them out
 
 template <typename W> struct GemvChunk;                // one 16-byte piece of a weight row
@@ -111,72 +115,103 @@ __device__ __forceinline__ void gemv_preload(const GemvArgs& a, int gw, int nw, 
     for (int j = 0; j < D; ++j) gemv_issue<W, MODE, D>(a, p, j, nw, n_units, nchunks, S);
 }
 
-// Activations -> LDS (fp32), optionally RMS-normalised: x / sqrt(mean(x^2) + eps) * gain.
-// COHERENT: read the input with agent-scope loads (it was written by other workgroups of the
-// same launch).  The caller synchronises the workgroup afterwards.
-// Split in two so that a kernel can put its weight preload between the input loads and the
-// reduction: gemv_stage_load copies the input into LDS and returns each thread's partial sums of
-// squares, gemv_stage_norm finishes the RMSNorm in place.
-template <typename W, int NC, bool NORM, bool COHERENT, int THREADS>
-__device__ __forceinline__ void gemv_stage_load(const GemvArgs& a, float4* xs, float (&ss)[NC]) {
-    const int K = a.K;
-    const int f4_per_col = gemv_f4_per_col<W>(K);
-    const int f4_used = K / 4;                        // logical float4s that hold data; the rest of the image is zero
-    const int tid = threadIdx.x;
+// Activations -> LDS (fp32), in two halves so that a kernel can put its weight preload in between:
+// the activation loads are issued FIRST and therefore return first (vector memory returns in order
+// within a wave, and the memory system is a queue: a load issued behind 16 KiB per wave of weight
+// loads comes back several microseconds later).
+//   gemv_stage_issue:  each of THREADS threads issues up to R float4 loads per column (+ gains);
+//   gemv_stage_commit: writes them to LDS (x * gain when NORM), handles what exceeds R * THREADS
+//                      float4s in further rounds, and leaves each wave's partial sum of squares in red.
+// After the workgroup barrier that must follow, gemv_inv_rms gives 1/sqrt(mean(x^2) + eps) per column;
+// it is applied to the finished dot products.  COHERENT: the input was written by other workgroups of
+// the same launch and is read with agent-scope loads.
+template <int NC, int R>
+struct GemvStageRegs {
+    float4 v[NC][R];
+    float4 g[R];
+};
+
+template <bool COHERENT>
+__device__ __forceinline__ float4 gemv_load_f4(const float* src) {
+    if (COHERENT) {
+        const unsigned long long lo = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long hi = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return make_float4(__uint_as_float((unsigned)lo), __uint_as_float((unsigned)(lo >> 32)),
+                           __uint_as_float((unsigned)hi), __uint_as_float((unsigned)(hi >> 32)));
+    }
+    return *reinterpret_cast<const float4*>(src);
+}
+
+template <int NC, bool NORM, bool COHERENT, int THREADS, int R>
+__device__ __forceinline__ void gemv_stage_issue(const GemvArgs& a, int tid, GemvStageRegs<NC, R>& regs) {
+    const int f4_used = a.K / 4;
 #pragma unroll
-    for (int n = 0; n < NC; ++n) ss[n] = 0.f;
-    for (int i4 = tid; i4 < f4_per_col; i4 += THREADS) {
-        const int dst = gemv_f4_index<W>(i4 * 4);
+    for (int r = 0; r < R; ++r) {
+        const int i4 = tid + r * THREADS;
+        regs.g[r] = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (NORM && i4 < f4_used) regs.g[r] = *reinterpret_cast<const float4*>(a.gain + i4 * 4);
 #pragma unroll
         for (int n = 0; n < NC; ++n) {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n < a.ncols && i4 < f4_used) {
-                const float* src = a.x + (size_t)n * a.x_stride + i4 * 4;
-                if (COHERENT) {
-                    const unsigned long long lo = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    const unsigned long long hi = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    v.x = __uint_as_float((unsigned)lo); v.y = __uint_as_float((unsigned)(lo >> 32));
-                    v.z = __uint_as_float((unsigned)hi); v.w = __uint_as_float((unsigned)(hi >> 32));
-                } else {
-                    v = *reinterpret_cast<const float4*>(src);
-                }
-            }
-            if (NORM) ss[n] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-            xs[n * f4_per_col + dst] = v;
+            regs.v[n][r] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n < a.ncols && i4 < f4_used) regs.v[n][r] = gemv_load_f4<COHERENT>(a.x + (size_t)n * a.x_stride + i4 * 4);
         }
     }
 }
 
-template <typename W, int NC, bool NORM, int THREADS>
-__device__ __forceinline__ void gemv_stage_norm(const GemvArgs& a, float4* xs, float (&ss)[NC], float (*red)[THREADS / 64]) {
+template <typename W, int NC, bool NORM, bool COHERENT, int THREADS, int R>
+__device__ __forceinline__ void gemv_stage_commit(const GemvArgs& a, int tid, float4* xs, GemvStageRegs<NC, R>& regs,
+                                                  float (*red)[THREADS / 64]) {
     const int K = a.K;
-    const int f4_per_col = gemv_f4_per_col<W>(K);
+    const int f4_per_col = gemv_f4_per_col<W>(K);     // slots of the image; those past K/4 are the zero tail
     const int f4_used = K / 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float ss[NC];
+#pragma unroll
+    for (int n = 0; n < NC; ++n) ss[n] = 0.f;
+    auto put = [&](int i4, int n, float4 t, const float4& g) {
+        if (NORM) {
+            ss[n] += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+            t.x *= g.x; t.y *= g.y; t.z *= g.z; t.w *= g.w;
+        }
+        xs[n * f4_per_col + gemv_f4_index<W>(i4 * 4)] = t;
+    };
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i4 = tid + r * THREADS;
+        if (i4 < f4_per_col) {
+#pragma unroll
+            for (int n = 0; n < NC; ++n) put(i4, n, regs.v[n][r], regs.g[r]);
+        }
+    }
+    for (int i4 = tid + R * THREADS; i4 < f4_per_col; i4 += THREADS) {      // wide inputs: the rest, one at a time
+        float4 g = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (NORM && i4 < f4_used) g = *reinterpret_cast<const float4*>(a.gain + i4 * 4);
+#pragma unroll
+        for (int n = 0; n < NC; ++n) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (n < a.ncols && i4 < f4_used) t = gemv_load_f4<COHERENT>(a.x + (size_t)n * a.x_stride + i4 * 4);
+            put(i4, n, t, g);
+        }
+    }
     if (NORM) {
+        const int lane = tid & 63, wave = tid >> 6;
 #pragma unroll
         for (int n = 0; n < NC; ++n) {
             const float s = wave_sum(ss[n]);
             if (lane == 0) red[n][wave] = s;
         }
-        __syncthreads();
-        float rinv[NC];
+    }
+}
+
+template <int NC, bool NORM, int WAVES>
+__device__ __forceinline__ void gemv_inv_rms(const GemvArgs& a, float (*red)[WAVES], float (&rinv)[NC]) {
 #pragma unroll
-        for (int n = 0; n < NC; ++n) {
+    for (int n = 0; n < NC; ++n) {
+        rinv[n] = 1.0f;
+        if (NORM) {
             float s = 0.f;
 #pragma unroll
-            for (int w = 0; w < THREADS / 64; ++w) s += red[n][w];
-            rinv[n] = 1.0f / sqrtf(s / (float)K + a.eps);
-        }
-        for (int i4 = tid; i4 < f4_used; i4 += THREADS) {   // each thread rescales what it wrote
-            const int dst = gemv_f4_index<W>(i4 * 4);
-            const float4 g = *reinterpret_cast<const float4*>(a.gain + i4 * 4);
-#pragma unroll
-            for (int n = 0; n < NC; ++n) {
-                float4 v = xs[n * f4_per_col + dst];
-                v.x *= rinv[n] * g.x; v.y *= rinv[n] * g.y; v.z *= rinv[n] * g.z; v.w *= rinv[n] * g.w;
-                xs[n * f4_per_col + dst] = v;
-            }
+            for (int w = 0; w < WAVES; ++w) s += red[n][w];
+            rinv[n] = 1.0f / sqrtf(s / (float)a.K + a.eps);
         }
     }
 }
@@ -240,9 +275,8 @@ template <int MODE, bool COHERENT>
 __device__ __forceinline__ void gemv_epilogue(const GemvArgs& a, int n, int row, float s0, float s1) {
     float* o = a.out + (size_t)n * a.out_stride + row;
     auto put = [](float* p, float v) { if (COHERENT) st_agent(p, v); else *p = v; };
-    auto get = [](const float* p) { return COHERENT ? ld_agent(p) : *p; };
     if (MODE == MODE_STORE) { put(o, s0); put(o + 1, s1); }
-    else if (MODE == MODE_RESID) { const float x0 = get(o), x1 = get(o + 1); put(o, x0 + s0); put(o + 1, x1 + s1); }
+    else if (MODE == MODE_RESID) { }                   // handled in gemv_run with the prefetched residual
     else if (MODE == MODE_SWIGLU) { put(o, s0 / (1.0f + expf(-s0)) * s1); }
     else {
         // rows (j, j + hd/2) of one head: rotate q and k by the column's position, append k and v
@@ -284,7 +318,8 @@ __device__ __forceinline__ void gemv_flush(const GemvArgs& a, const GemvEpBuf<NC
 
 // Main loop of a phase: consume the wave's steps, keeping the ring full.  `ep` is this wave's buffer.
 template <typename W, int NC, int MODE, int D, bool COHERENT>
-__device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, int gw, int nw, GemvPipe<W, D>& p, GemvEpBuf<NC>& ep) {
+__device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, int gw, int nw, GemvPipe<W, D>& p, GemvEpBuf<NC>& ep,
+                                         const float (&scale)[NC]) {
     const int lane = threadIdx.x & 63;
     const int f4_per_col = gemv_f4_per_col<W>(a.K);
     const int nchunks = a.K / GemvChunk<W>::N;
@@ -292,6 +327,25 @@ __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, in
     const int n_units = gemv_n_units(a, MODE);
     const int total = p.total;
     int cu = gw, cit = 0, n_ep = 0;
+    // residual mode: lane e fetches the old values of the rows of this wave's e-th unit now, long before they are needed
+    float res0[NC], res1[NC];
+    if (MODE == MODE_RESID) {
+        const int e_unit = gw + lane * nw;
+#pragma unroll
+        for (int n = 0; n < NC; ++n) {
+            res0[n] = 0.f; res1[n] = 0.f;
+            if (e_unit < n_units && n < a.ncols) {
+                const float* o = a.out + (size_t)n * a.out_stride + 2 * e_unit;
+                if (COHERENT) {
+                    const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(o), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    res0[n] = __uint_as_float((unsigned)bits); res1[n] = __uint_as_float((unsigned)(bits >> 32));
+                } else {
+                    const float2 v = *reinterpret_cast<const float2*>(o);
+                    res0[n] = v.x; res1[n] = v.y;
+                }
+            }
+        }
+    }
     float acc0[NC], acc1[NC];
 #pragma unroll
     for (int n = 0; n < NC; ++n) { acc0[n] = 0.f; acc1[n] = 0.f; }
@@ -304,7 +358,7 @@ __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, in
             gemv_unit_rows<W, MODE>(a, cu, r0, r1, row);
 #pragma unroll
             for (int n = 0; n < NC; ++n) {
-                const float s0 = wave_sum(acc0[n]), s1 = wave_sum(acc1[n]);
+                const float s0 = wave_sum(acc0[n]) * scale[n], s1 = wave_sum(acc1[n]) * scale[n];
                 if (lane == 0) { ep.s[n_ep][n][0] = s0; ep.s[n_ep][n][1] = s1; }
                 acc0[n] = 0.f; acc1[n] = 0.f;
             }
@@ -334,7 +388,21 @@ __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, in
         }
     }
     __builtin_amdgcn_wave_barrier();
-    gemv_flush<NC, MODE, COHERENT>(a, ep, n_ep);
+    if (MODE == MODE_RESID) {
+        // lane e owns parked unit e (n_ep <= 64): add the prefetched residual and store, no load on the way out
+        if (lane < n_ep) {
+#pragma unroll
+            for (int n = 0; n < NC; ++n) {
+                if (n < a.ncols) {
+                    float* o = a.out + (size_t)n * a.out_stride + ep.row[lane];
+                    const float y0 = res0[n] + ep.s[lane][n][0], y1 = res1[n] + ep.s[lane][n][1];
+                    if (COHERENT) { st_agent(o, y0); st_agent(o + 1, y1); } else { o[0] = y0; o[1] = y1; }
+                }
+            }
+        }
+    } else {
+        gemv_flush<NC, MODE, COHERENT>(a, ep, n_ep);
+    }
 }
 
 }  // namespace d3

@@ -7,8 +7,9 @@
 // finished with a wave reduction.  The RMSNorm of the input (fused QKV, gate/up
 // and lm_head projections) is recomputed by every workgroup in its prologue: the
 // input is a few KiB that stay in L2, which is cheaper than a separate launch.
-// A wave issues the loads of its first weight rows before that prologue, so the
-// HBM latency of a fresh launch overlaps the staging of the activations.
+// Each wave issues its share of the activation loads first and the loads of its first
+// weight rows right behind them, so the two latencies overlap and the activations, being
+// first in the queue, arrive first.
 //
 // Epilogues: plain store; residual add; SiLU(gate)*up; and, for the fused QKV
 // projection, the rotary embedding plus the append of the new K/V row to the
@@ -24,15 +25,22 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_alu_kernel(GemvArgs a) {
     extern __shared__ float4 xs[];                     // [NC][f4_per_col]
     __shared__ float red[NC][kGemvWaves];
     __shared__ GemvEpBuf<NC> ep[kGemvWaves];
-    const int wave = threadIdx.x >> 6;
+    constexpr int R = kGemvStageR / NC;
+    const int tid = threadIdx.x, wave = tid >> 6;
     const int gw = blockIdx.x * kGemvWaves + wave, nw = gridDim.x * kGemvWaves;
+    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 0] = wall_clock64();
+    GemvStageRegs<NC, R> regs;
     GemvPipe<W, kGemvDepth> pipe;
-    float ss[NC];
-    gemv_stage_load<W, NC, NORM, false, kGemvThreads>(a, xs, ss);
-    gemv_preload<W, MODE, kGemvDepth>(a, gw, nw, pipe);          // weights start streaming while the norm is reduced
-    gemv_stage_norm<W, NC, NORM, kGemvThreads>(a, xs, ss, red);
+    gemv_stage_issue<NC, NORM, false, kGemvThreads, R>(a, tid, regs);          // activations first ...
+    for (int i = 0; i < a.head_start; ++i) __builtin_amdgcn_s_sleep(8);          // ... with a head start over every workgroup's weights
+    gemv_preload<W, MODE, kGemvDepth>(a, gw, nw, pipe);                          // ... the weight stream right behind them
+    gemv_stage_commit<W, NC, NORM, false, kGemvThreads, R>(a, tid, xs, regs, red);
     __syncthreads();
-    gemv_run<W, NC, MODE, kGemvDepth, false>(a, xs, gw, nw, pipe, ep[wave]);
+    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 1] = wall_clock64();
+    float rinv[NC];
+    gemv_inv_rms<NC, NORM, kGemvWaves>(a, red, rinv);
+    gemv_run<W, NC, MODE, kGemvDepth, false>(a, xs, gw, nw, pipe, ep[wave], rinv);
+    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 2] = wall_clock64();
 }
 
 template <typename W, int NC>
@@ -42,7 +50,7 @@ int launch_nc(const GemvArgs& a, int mode, bool norm, int n_wg, hipStream_t s) {
     int grid = (n_units + kGemvWaves - 1) / kGemvWaves;
     if (grid > n_wg) grid = n_wg;
     if (grid < 1) grid = 1;
-    if ((long long)grid * kGemvWaves * kGemvEpCap < n_units) return (int)hipErrorInvalidValue;   // a wave parks at most kGemvEpCap units
+    if ((long long)grid * kGemvWaves * kGemvEpCap < n_units) return (int)hipErrorInvalidValue;   // a wave parks at most kGemvEpCap (= 64 lanes) units
 #define D3_LAUNCH(MODE, NORM) hipLaunchKernelGGL((gemv_alu_kernel<W, NC, MODE, NORM>), dim3(grid), dim3(kGemvThreads), lds, s, a)
     if (mode == MODE_STORE) { if (norm) D3_LAUNCH(MODE_STORE, true); else D3_LAUNCH(MODE_STORE, false); }
     else if (mode == MODE_RESID) { D3_LAUNCH(MODE_RESID, false); }

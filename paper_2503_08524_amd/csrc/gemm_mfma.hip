@@ -3,12 +3,16 @@
 //
 // The weight matrix is the MFMA "A" operand (16 rows per tile), the activation columns the
 // "B" operand (16 columns per tile, one or two tiles).  Weights are read from HBM exactly
-// once, 16 bytes per lane; a workgroup owns one 16-row tile (a gate tile and its up tile
-// for SwiGLU) and its waves split K between them, 128 consecutive k per wave per turn, so
-// that a narrow matrix still puts thousands of waves on the memory system.  Partial tiles
-// are summed through LDS.  Activations arrive pre-split as x = hi + lo (two bf16 halves,
-// ~16 mantissa bits): two MFMAs per weight tile keep fp32-like accuracy, and the matrix
-// cores have an order of magnitude of headroom on this HBM-bound contraction.
+// once, 16 bytes per lane.  A workgroup owns RT consecutive 16-row tiles (RT gate tiles and
+// their up tiles for SwiGLU) and its waves split K between them, 128 consecutive k per wave
+// per turn, so that a narrow matrix still puts thousands of waves on the memory system; a
+// wave reuses each activation fragment for all its RT tiles, which keeps the L2 traffic of
+// the activations below the HBM traffic of the weights.  Tiles are fetched with coalesced loads and
+// re-shaped into MFMA fragments through a small per-wave LDS tile; the next turn's loads are in
+// flight while the current turn's MFMAs run.  Partial tiles are summed
+// through LDS.  Activations arrive pre-split as x = hi + lo (two bf16 halves, ~16 mantissa
+// bits): two MFMAs per weight tile keep fp32-like accuracy, and the matrix cores have an
+// order of magnitude of headroom on this HBM-bound contraction.
 //
 // v_mfma_f32_16x16x32_bf16 operand layout (lane l, i = l % 16, g = l / 16): A holds row i,
 // k = 8g..8g+7; B holds column i, the same k; the result holds column i, rows 4g..4g+3.
@@ -21,87 +25,148 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int U = 4;   // k-steps (of 32) a wave takes per turn: 256 contiguous bytes of each weight row
+constexpr int U = 4;            // k-steps (of 32) a wave takes per turn: 256 contiguous bytes of each row
+constexpr int kTileRowBytes = 272;   // LDS pitch of a staged 16 x 256 B tile (+16 B: conflict-free fragment reads)
+constexpr int kTileBytes = 16 * kTileRowBytes;
 
-template <int NT, int MODE>
-__global__ __launch_bounds__(1024) void gemm_mfma_kernel(GemvArgs a) {
-    constexpr int RT = (MODE == MODE_SWIGLU) ? 2 : 1;
-    constexpr int A = RT * NT * 4;                    // accumulator floats per lane
-    extern __shared__ float red[];                    // [waves][A][64]
+// A 16-row x 128-k bf16 tile travels global -> registers (coalesced: 16 lanes read 256 contiguous bytes
+// of one row, four rows per instruction) -> this wave's LDS tile -> MFMA fragments (lane (i, g) gets row i,
+// k = 32u + 8g .. + 7 for the turn's k-step u).  Reading the fragments straight from global memory would
+// make neighbouring lanes touch 16 different rows per instruction, which the memory pipeline punishes.
+struct TileRegs { u32x4 q[4]; };
+
+__device__ __forceinline__ void tile_load(TileRegs& r, const bf16_t* row0_k0, size_t row_stride, int k0, int K) {
+    const int lane = threadIdx.x & 63;
+    int k = k0 + (lane & 15) * 8;
+    k = k <= K - 8 ? k : K - 8;                        // a ragged last turn re-reads valid bytes (those k-steps are skipped)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.q[q] = load_stream16(row0_k0 + (size_t)(4 * q + (lane >> 4)) * row_stride + (k - k0));
+}
+__device__ __forceinline__ void tile_load_cached(TileRegs& r, const bf16_t* row0_k0, size_t row_stride, int k0, int K) {
+    const int lane = threadIdx.x & 63;
+    int k = k0 + (lane & 15) * 8;
+    k = k <= K - 8 ? k : K - 8;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint4 v = *reinterpret_cast<const uint4*>(row0_k0 + (size_t)(4 * q + (lane >> 4)) * row_stride + (k - k0));
+        r.q[q] = u32x4{v.x, v.y, v.z, v.w};
+    }
+}
+__device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32x4 (&frag)[U]) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        *reinterpret_cast<u32x4*>(tile + (4 * q + (lane >> 4)) * kTileRowBytes + (lane & 15) * 16) = r.q[q];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        frag[u] = *reinterpret_cast<const u32x4*>(tile + (lane & 15) * kTileRowBytes + u * 64 + (lane >> 4) * 16);
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int NT, int MODE, int RT>
+__global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 waves
+    constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;  // weight matrices per output tile
+    constexpr int NA = RT * SW;                        // A tiles per wave
+    constexpr int NB = 2 * NT;                         // B tiles per wave and turn (hi and lo of each column tile)
+    constexpr int ACC = NA * NT * 4;                   // accumulator floats per lane
+    extern __shared__ float red[];                     // [waves][ACC][64] for the final sum; first, one staging tile per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
-    const int i = lane & 15, g = lane >> 4;
-    const int K = a.K, row0 = blockIdx.x * 16;
+    const int K = a.K, row0 = blockIdx.x * (16 * RT);
+    char* tile = reinterpret_cast<char*>(red) + (size_t)wave * kTileBytes;
 
-    const bf16_t* wr[RT];
-    if (MODE == MODE_SWIGLU) {
-        wr[0] = static_cast<const bf16_t*>(a.w[0]) + (size_t)(row0 + i) * K + 8 * g;
-        wr[RT - 1] = static_cast<const bf16_t*>(a.w[1]) + (size_t)(row0 + i) * K + 8 * g;
-    } else {
-        int m = 0, local = row0;
-        if (local >= a.rows[0]) { local -= a.rows[0]; m = 1; if (local >= a.rows[1]) { local -= a.rows[1]; m = 2; } }
-        wr[0] = static_cast<const bf16_t*>(a.w[m]) + (size_t)(local + i) * K + 8 * g;
-    }
-    const bf16_t* xh[NT];
-    const bf16_t* xl[NT];
+    const bf16_t* wrow[NA];                            // row 0 of each A tile
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        xh[t] = a.x_hi + (size_t)(t * 16 + i) * a.x_stride + 8 * g;
-        xl[t] = a.x_lo + (size_t)(t * 16 + i) * a.x_stride + 8 * g;
+    for (int r = 0; r < RT; ++r) {
+        if (MODE == MODE_SWIGLU) {
+            wrow[r * SW] = static_cast<const bf16_t*>(a.w[0]) + (size_t)(row0 + r * 16) * K;
+            wrow[r * SW + SW - 1] = static_cast<const bf16_t*>(a.w[1]) + (size_t)(row0 + r * 16) * K;
+        } else {
+            int m = 0, local = row0 + r * 16;
+            if (local >= a.rows[0]) { local -= a.rows[0]; m = 1; if (local >= a.rows[1]) { local -= a.rows[1]; m = 2; } }
+            wrow[r] = static_cast<const bf16_t*>(a.w[m]) + (size_t)local * K;
+        }
     }
 
-    f32x4 acc[RT][NT];
+    f32x4 acc[NA][NT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
+    for (int r = 0; r < NA; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t) acc[r][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int nks = K / 32;
-    for (int ks0 = wave * U; ks0 < nks; ks0 += n_waves * U) {
-        u32x4 wv[RT][U];
+    const int stride = n_waves * U;
+    TileRegs ga[NA], gb[NB];                           // the loads of one turn, in flight while the previous turn computes
+    auto issue = [&](int ks0) {
+        const int k0 = ks0 * 32;
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (ks0 + u < nks) {
-#pragma unroll
-                for (int r = 0; r < RT; ++r)
-                    wv[r][u] = load_stream16(wr[r] + (size_t)(ks0 + u) * 32);
-            }
+        for (int t = 0; t < NT; ++t) {
+            tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
+            tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (ks0 + u < nks) {
+        for (int r = 0; r < NA; ++r) tile_load(ga[r], wrow[r] + k0, K, k0, K);
+    };
+    // consume the turn held in ga/gb; when NEXT, re-issue each register set for turn ks_next as soon as it is in LDS
+    auto turn = [&](int ks0, bool next, int ks_next) {
+        u32x4 bf[NB][U];
+        const int k1 = ks_next * 32;
 #pragma unroll
-                for (int t = 0; t < NT; ++t) {
-                    const uint4 bh = *reinterpret_cast<const uint4*>(xh[t] + (size_t)(ks0 + u) * 32);
-                    const uint4 bl = *reinterpret_cast<const uint4*>(xl[t] + (size_t)(ks0 + u) * 32);
+        for (int t = 0; t < NT; ++t) {
+            tile_to_frags(gb[2 * t], tile, bf[2 * t]);
+            if (next) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+            tile_to_frags(gb[2 * t + 1], tile, bf[2 * t + 1]);
+            if (next) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+        }
 #pragma unroll
-                    for (int r = 0; r < RT; ++r) {
-                        const bf16x8 wa = __builtin_bit_cast(bf16x8, wv[r][u]);
-                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bh), acc[r][t], 0, 0, 0);
-                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bl), acc[r][t], 0, 0, 0);
+        for (int r = 0; r < NA; ++r) {
+            u32x4 af[U];
+            tile_to_frags(ga[r], tile, af);
+            if (next) tile_load(ga[r], wrow[r] + k1, K, k1, K);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (ks0 + u < nks) {
+                    const bf16x8 wa = __builtin_bit_cast(bf16x8, af[u]);
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) {
+                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bf[2 * t][u]), acc[r][t], 0, 0, 0);
+                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bf[2 * t + 1][u]), acc[r][t], 0, 0, 0);
                     }
                 }
             }
         }
+    };
+
+    int ks0 = wave * U;
+    if (ks0 < nks) {
+        issue(ks0);
+        while (ks0 + stride < nks) {                   // steady state: every register set is re-issued unconditionally
+            turn(ks0, true, ks0 + stride);
+            ks0 += stride;
+        }
+        turn(ks0, false, 0);
     }
+    __syncthreads();                                   // the staging tiles give way to the partial sums
 
     // ---- sum the waves' partial tiles through LDS, then the epilogue ----
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
+    for (int r = 0; r < NA; ++r)
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) red[((size_t)wave * A + (r * NT + t) * 4 + e) * 64 + lane] = acc[r][t][e];
+            for (int e = 0; e < 4; ++e) red[((size_t)wave * ACC + (r * NT + t) * 4 + e) * 64 + lane] = acc[r][t][e];
     __syncthreads();
-    constexpr int A_OUT = NT * 4;                     // outputs per lane (gate/up pairs fold into one)
-    for (int idx = tid; idx < A_OUT * 64; idx += blockDim.x) {
-        const int ai = idx >> 6, l = idx & 63;
+    constexpr int OUT = RT * NT * 4;                   // outputs per lane (a gate/up pair folds into one)
+    for (int idx = tid; idx < OUT * 64; idx += blockDim.x) {
+        const int oi_ = idx >> 6, l = idx & 63;
+        const int r = oi_ / (NT * 4), t = (oi_ >> 2) % NT, e = oi_ & 3;
+        const int a0 = ((r * SW) * NT + t) * 4 + e;     // accumulator slot of the (gate) tile
         float s0 = 0.f, s1 = 0.f;
         for (int w = 0; w < n_waves; ++w) {
-            s0 += red[((size_t)w * A + ai) * 64 + l];
-            if (MODE == MODE_SWIGLU) s1 += red[((size_t)w * A + A_OUT + ai) * 64 + l];
+            s0 += red[((size_t)w * ACC + a0) * 64 + l];
+            if (MODE == MODE_SWIGLU) s1 += red[((size_t)w * ACC + a0 + NT * 4) * 64 + l];
         }
-        const int t = ai >> 2, e = ai & 3;
-        const int row = row0 + 4 * (l >> 4) + e, col = t * 16 + (l & 15);
+        const int row = row0 + r * 16 + 4 * (l >> 4) + e, col = t * 16 + (l & 15);
         if (col >= a.ncols) continue;
         const size_t oi = (size_t)col * a.out_stride + row;
         float v;
@@ -117,6 +182,16 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kernel(GemvArgs a) {
     }
 }
 
+template <int NT, int MODE>
+int launch_rt(const GemvArgs& a, int rt, int tiles, int waves, size_t lds, hipStream_t s) {
+#define D3_LAUNCH(RT) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE, RT>), dim3(tiles / RT), dim3(64 * waves), lds, s, a)
+    if (rt == 4) { if (MODE == MODE_SWIGLU) return (int)hipErrorInvalidValue; D3_LAUNCH((MODE == MODE_SWIGLU ? 2 : 4)); }
+    else if (rt == 2) D3_LAUNCH(2);
+    else D3_LAUNCH(1);
+#undef D3_LAUNCH
+    return (int)hipGetLastError();
+}
+
 }  // namespace
 
 // Requirements (checked by the caller): bf16 weights; K % 32 == 0; total_rows and every rows[m]
@@ -125,20 +200,36 @@ __global__ __launch_bounds__(1024) void gemm_mfma_kernel(GemvArgs a) {
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
-    const int rt = mode == MODE_SWIGLU ? 2 : 1;
-    int waves = 4;
-    while (waves < 16 && tiles * waves < 8 * n_cu) waves *= 2;
-    while (waves > 4 && (a.K / 32) < waves * U) waves /= 2;                       // at least one turn per wave
-    while (waves > 4 && (size_t)waves * rt * nt * 4 * 64 * sizeof(float) > 48 * 1024) waves /= 2;
-    const size_t lds = (size_t)waves * rt * nt * 4 * 64 * sizeof(float);
-#define D3_LAUNCH(NT, MODE) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE>), dim3(tiles), dim3(64 * waves), lds, s, a)
-    if (nt == 1) {
-        if (mode == MODE_STORE) D3_LAUNCH(1, MODE_STORE); else if (mode == MODE_RESID) D3_LAUNCH(1, MODE_RESID); else D3_LAUNCH(1, MODE_SWIGLU);
-    } else {
-        if (mode == MODE_STORE) D3_LAUNCH(2, MODE_STORE); else if (mode == MODE_RESID) D3_LAUNCH(2, MODE_RESID); else D3_LAUNCH(2, MODE_SWIGLU);
+    const int sw = mode == MODE_SWIGLU ? 2 : 1;
+    const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
+    // Most tiles per workgroup (activation reuse) that still leaves >= 6 waves per CU, within 32 KiB of
+    // LDS for the cross-wave sum; stacked matrices must not share a workgroup (rows[m] % (16 RT) == 0).
+    int best_rt = 1, best_waves = 4;
+    const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave
+    for (int rt = rt_max; rt >= 1; rt /= 2) {
+        if (tiles % rt != 0) continue;
+        bool aligned = true;
+        if (mode != MODE_SWIGLU)
+            for (int m = 0; m < 3; ++m)
+                if (a.rows[m] % (16 * rt) != 0) aligned = false;
+        if (!aligned) continue;
+        int waves = 32 / (rt * nt * sw);
+        if (waves > 8) waves = 8;
+        while (waves > 4 && waves > turns) waves /= 2;         // at least one turn per wave
+        if (waves < 4) continue;
+        best_rt = rt; best_waves = waves;
+        if ((long long)(tiles / rt) * waves >= 6LL * n_cu) break;
     }
-#undef D3_LAUNCH
-    return (int)hipGetLastError();
+    size_t lds = (size_t)best_waves * best_rt * sw * nt * 4 * 64 * sizeof(float);   // cross-wave sum ...
+    if (lds < (size_t)best_waves * kTileBytes) lds = (size_t)best_waves * kTileBytes;    // ... or one staging tile per wave
+    if (nt == 1) {
+        if (mode == MODE_STORE) return launch_rt<1, MODE_STORE>(a, best_rt, tiles, best_waves, lds, s);
+        if (mode == MODE_RESID) return launch_rt<1, MODE_RESID>(a, best_rt, tiles, best_waves, lds, s);
+        return launch_rt<1, MODE_SWIGLU>(a, best_rt, tiles, best_waves, lds, s);
+    }
+    if (mode == MODE_STORE) return launch_rt<2, MODE_STORE>(a, best_rt, tiles, best_waves, lds, s);
+    if (mode == MODE_RESID) return launch_rt<2, MODE_RESID>(a, best_rt, tiles, best_waves, lds, s);
+    return launch_rt<2, MODE_SWIGLU>(a, best_rt, tiles, best_waves, lds, s);
 }
 
 }  // namespace d3

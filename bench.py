@@ -127,6 +127,14 @@ def main() -> int:
     dec = binding.Decoder(shape, weights, B, P + G, kv_dtype=kv, device=dev)
     prompts = torch.from_numpy(d3_inputs.make_prompt(B, P, shape.V, seed=1)).to(dev)
 
+    # a plain device-to-device copy of known size (1 GiB read + 1 GiB written): the yardstick that scales the
+    # FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     dec.set_plan(alphas[0], start, 0, G)
     torch.cuda.synchronize()
     t0 = time.perf_counter()

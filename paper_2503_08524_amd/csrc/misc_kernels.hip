@@ -21,35 +21,75 @@ __global__ __launch_bounds__(256) void embed_kernel(const W* __restrict__ emb, c
     int tok = tokens[cm.tok_index(c)];
     tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);   // stay inside the table whatever the caller fed
     const W* row = emb + (size_t)tok * d;
-    for (int j = threadIdx.x; j < d; j += blockDim.x) {
-        float v;
-        if (sizeof(W) == 4) v = reinterpret_cast<const float*>(row)[j];
-        else v = bf16_to_f32(reinterpret_cast<const bf16_t*>(row)[j]);
-        x[(size_t)c * d + j] = v;
+    float* xo = x + (size_t)c * d;
+    if (sizeof(W) == 4) {
+        for (int j = threadIdx.x * 4; j < d; j += blockDim.x * 4)
+            *reinterpret_cast<float4*>(xo + j) = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(row) + j);
+    } else {
+        for (int j = threadIdx.x * 8; j < d; j += blockDim.x * 8) {       // d % 8 == 0: eight bf16 per load
+            const uint4 v = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(row) + j);
+            *reinterpret_cast<float4*>(xo + j) = make_float4(bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y));
+            *reinterpret_cast<float4*>(xo + j + 4) = make_float4(bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w));
+        }
     }
 }
 
 // ---------------- RMSNorm (optional) + split into bf16 hi/lo ----------------
+// One workgroup per column.  A thread keeps up to 8 float4 of the column in registers (all loads
+// issued together), so the column is read once; wider columns fall back to a second read.
 __global__ __launch_bounds__(256) void norm_split_kernel(const float* __restrict__ x, int x_stride,
                                                          const float* __restrict__ gain, float eps, int K,
                                                          bf16_t* __restrict__ hi, bf16_t* __restrict__ lo) {
+    constexpr int R = 8;
     __shared__ float red[4];
     const int c = blockIdx.x, tid = threadIdx.x;
     const float* xc = x + (size_t)c * x_stride;
+    const int n4 = K / 4;
+    float4 v[R], g[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i4 = tid + r * 256;
+        v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        g[r] = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (i4 < n4) {
+            v[r] = *reinterpret_cast<const float4*>(xc + i4 * 4);
+            if (gain) g[r] = *reinterpret_cast<const float4*>(gain + i4 * 4);
+        }
+    }
     float rinv = 1.0f;
     if (gain) {
         float ss = 0.f;
-        for (int j = tid; j < K; j += 256) ss += xc[j] * xc[j];
+#pragma unroll
+        for (int r = 0; r < R; ++r) ss += v[r].x * v[r].x + v[r].y * v[r].y + v[r].z * v[r].z + v[r].w * v[r].w;
+        for (int i4 = tid + R * 256; i4 < n4; i4 += 256) {
+            const float4 t = *reinterpret_cast<const float4*>(xc + i4 * 4);
+            ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+        }
         ss = wave_sum(ss);
         if ((tid & 63) == 0) red[tid >> 6] = ss;
         __syncthreads();
         rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
     }
-    for (int j = tid; j < K; j += 256) {
-        const float v = gain ? xc[j] * rinv * gain[j] : xc[j];
-        const uint32_t h = f32_to_bf16(v);
-        hi[(size_t)c * K + j] = (bf16_t)h;
-        lo[(size_t)c * K + j] = (bf16_t)f32_to_bf16(v - bf16_to_f32(h));
+    auto emit = [&](int i4, const float4& t, const float4& gg) {
+        const float f[4] = {t.x * rinv * gg.x, t.y * rinv * gg.y, t.z * rinv * gg.z, t.w * rinv * gg.w};
+        uint32_t h[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h[e] = f32_to_bf16(f[e]);
+            l[e] = f32_to_bf16(f[e] - bf16_to_f32(h[e]));
+        }
+        *reinterpret_cast<uint2*>(hi + (size_t)c * K + i4 * 4) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+        *reinterpret_cast<uint2*>(lo + (size_t)c * K + i4 * 4) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+    };
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i4 = tid + r * 256;
+        if (i4 < n4) emit(i4, v[r], g[r]);
+    }
+    for (int i4 = tid + R * 256; i4 < n4; i4 += 256) {
+        float4 gg = make_float4(1.f, 1.f, 1.f, 1.f);
+        if (gain) gg = *reinterpret_cast<const float4*>(gain + i4 * 4);
+        emit(i4, *reinterpret_cast<const float4*>(xc + i4 * 4), gg);
     }
 }
 
@@ -96,9 +136,21 @@ __global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ 
     const float* lg = logits + (size_t)c * vocab;
     float best = -INFINITY;
     int idx = 0x7fffffff;
-    for (int j = tid; j < vocab; j += 1024) {
-        const float v = lg[j];
-        if (v > best || (v == best && j < idx)) { best = v; idx = j; }
+    auto take = [&](float v, int j) { if (v > best || (v == best && j < idx)) { best = v; idx = j; } };
+    // vocab % 2 == 0: pairs, eight pair-loads in flight per thread
+    const int n2 = vocab / 2;
+    for (int base = 0; base < n2; base += 1024 * 8) {
+        float2 v[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int p = base + r * 1024 + tid;
+            v[r] = p < n2 ? *reinterpret_cast<const float2*>(lg + 2 * p) : make_float2(-INFINITY, -INFINITY);
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int p = base + r * 1024 + tid;
+            if (p < n2) { take(v[r].x, 2 * p); take(v[r].y, 2 * p + 1); }
+        }
     }
     // NaN logits never win (comparisons false); an all-NaN row yields index clamp below
 #pragma unroll

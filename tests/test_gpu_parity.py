@@ -91,3 +91,87 @@ def test_llama7b_widths_two_blocks_batch1(persistent):
 
 def test_llama7b_widths_two_blocks_batch4():
     _run(d3_inputs.LLAMA_7B.truncated(2), 4, 3, 3, 0.7, 1, forced_seed=13)
+
+
+def test_llama13b_widths_one_block_batch4():
+    # 13B widths, batch 4: the matrix-core path with one column tile at real K (5120 / 13824) and row counts
+    _run(d3_inputs.LLAMA_13B.truncated(1), 4, 2, 3, 1.0, 0, forced_seed=15)
+
+
+def test_llama70b_widths_one_block_gqa():
+    # 70B widths: grouped-query attention (64 query / 8 KV heads) and d_ffn 28672, which only the matrix-core
+    # path can take (batch 1 included); one set of weights serves both batch sizes
+    shape = d3_inputs.LLAMA_70B.truncated(1)
+    w = d3_inputs.make_weights(shape, 0)
+    for B in (2, 1):
+        prompts = d3_inputs.make_prompt(B, 2, shape.V, seed=1)
+        forced = _forced(B, 2, shape.V, 16)
+        print(f"case {shape.name} B={B}", flush=True)
+        gpu = helpers.gpu_generate(shape, w, prompts, 2, 1.0, 0, forced=forced)
+        _, gens = helpers.oracle_generate(shape, w, prompts, 2, 1.0, 0, forced=forced)
+        wl, wh = helpers.compare(gpu, gens, 2)
+        print(f"  worst logit abs err {wl:.3e}, worst hidden rel L2 {wh:.3e}", flush=True)
+        del gpu
+
+
+def test_full_size_7b_configuration_sampled_against_oracle():
+    """The benchmark's own launch configuration (7B shape, 32 blocks, batch 1, prompt 512) checked on the
+    outputs the oracle can afford: the hidden state after block 0 of the last prompt position and of every
+    decode step, and the complete logits of the steps that keep only block 0 / no block (alpha = 0.5 keeps
+    32, 16, 8, 4, 2, 1, 0 blocks).  All 32 blocks point at the same weight tensors, so the host draws one
+    block; the oracle runs that block alone over the 518 rows."""
+    import torch
+    from oracle import oracle
+    from paper_2503_08524_amd import binding
+
+    full = d3_inputs.LLAMA_7B
+    one = full.truncated(1)
+    w1 = d3_inputs.make_weights(one, 0)
+    w_tied = dict(w1)
+    w_tied["layers"] = [w1["layers"][0]] * full.L
+    P, G, alpha, start = 512, 7, 0.5, 19
+    prompts = d3_inputs.make_prompt(1, P, full.V, seed=1)
+    forced = _forced(1, G, full.V, 17)
+    keep, drop, ids = binding.d3_plan_depth(full.L, alpha, start, 0, G)
+    assert keep.tolist() == [32, 16, 8, 4, 2, 1, 0] and ids[5, 0] == 0
+
+    # GPU: the real thing, one device copy of the block shared by all 32 layer entries
+    dev = binding.weights_to_device(one, w1)
+    dev_tied = dict(dev)
+    dev_tied["layers"] = [dev["layers"][0]] * full.L
+    dec = binding.Decoder(full, dev_tied, 1, P + G)
+    print("case full-size 7B, tied blocks", flush=True)
+    gpu = helpers.gpu_generate(full, None, prompts, G, alpha, start, forced=forced, decoder=dec, fill_each_step=True)
+
+    # oracle: block 0 alone over every row
+    oracle.set_threads(helpers.oracle_threads())
+    model = oracle.OracleModel(one, w1)
+    seq = model.new_seq(P + G)
+    hid = None
+    for p in range(P):
+        hid, _ = seq.forward_token(int(prompts[0, p]), p, [0], want_hidden=(p == P - 1))
+    def rel(a, b):
+        return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+    assert rel(gpu["hidden"][0][1, 0].astype(np.float64), hid[1]) <= helpers.HIDDEN_REL_L2
+    worst = 0.0
+    for i in range(1, G):
+        blocks = [0] if keep[i] >= 1 else []
+        h, lg = seq.forward_token(int(forced[0, i - 1]), P + i - 1, blocks, want_hidden=True, want_logits=True)
+        got = gpu["hidden"][i][:, 0].astype(np.float64)
+        assert rel(got[0], h[0]) <= 1e-6                                   # the embedding row
+        if keep[i] >= 1:
+            assert rel(got[1], h[1]) <= helpers.HIDDEN_REL_L2, f"step {i}"
+        if keep[i] <= 1:                                                    # logits depend on block 0 at most
+            err = float(np.abs(gpu["logits"][i][0].astype(np.float64) - lg).max())
+            worst = max(worst, err)
+            assert err <= helpers.LOGIT_ATOL, f"step {i}: logits max abs err {err:.3e}"
+            top2 = np.partition(lg, -2)[-2:]
+            if top2[1] - top2[0] > helpers.TOKEN_MARGIN:
+                assert int(gpu["tokens"][i][0]) == oracle.argmax(lg)
+    print(f"  worst logit abs err {worst:.3e}", flush=True)
+    # the fill of the dropped blocks copied the source block's rows (bit-exact), at full cache size
+    for i in (1, 5):
+        pos, s, n = P + i - 1, int(drop[i]), full.L - int(keep[i])
+        src = s - 1
+        assert torch.equal(dec.k_cache[s, 0, :, pos], dec.k_cache[src, 0, :, pos])
+        assert torch.equal(dec.v_cache[s + n - 1, 0, :, pos], dec.v_cache[src, 0, :, pos])

@@ -177,8 +177,17 @@ def main() -> int:
     ms, n = dec.profile_read()
     dec.profile_select(binding.D3_K_NONE)
     achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9 if n else 0.0
+    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
+    # each scaled by what a plain 1 GiB copy reads on the same counter); only known for the profiled workload
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_7b_b1_hbm_traffic.json")
+    if args.config == "7b" and kclass == binding.D3_K_GATE_UP and os.path.exists(tpath):
+        with open(tpath) as f:
+            k = json.load(f)["kernels"].get("gemv_alu_kernel<unsigned short, 1, 2, true>")
+        if k:
+            traffic = k["fetch_bytes_per_launch"] + k["write_bytes_per_launch"]
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved,
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                 "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": bytes_per_launch}
 
     out = {

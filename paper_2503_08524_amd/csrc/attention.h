@@ -68,12 +68,22 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
     const float* cur_k = a.q + (size_t)c * a.q_stride + (size_t)(a.H + kvh) * HD + sub * EPL;
     const float* cur_v = cur_k + (size_t)a.H_kv * HD;
 
+    // q is loaded raw and first touched in the score loop, after the K/V loads have been issued
+    // (scaling it here would make those loads wait for it); 1/sqrt(hd) is applied to the scores
+    const float scale = 1.0f / sqrtf((float)HD);
     float qv[EPL];
     {
-        const float scale = 1.0f / sqrtf((float)HD);
         const float* qp = a.q + (size_t)c * a.q_stride + (size_t)h * HD + sub * EPL;
+        if (FUSED) {
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) qv[e] = (FUSED ? ld_agent(qp + e) : qp[e]) * scale;
+            for (int e = 0; e < EPL; ++e) qv[e] = ld_agent(qp + e);
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(qp + e);
+                qv[e] = t.x; qv[e + 1] = t.y; qv[e + 2] = t.z; qv[e + 3] = t.w;
+            }
+        }
     }
 
     const int iters = (n + RPB - 1) / RPB;
@@ -112,6 +122,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
                 for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
 #pragma unroll
                 for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+                s *= scale;
                 if (j < j1) { sv[u] = s; lmax = fmaxf(lmax, s); }
             }
         }
@@ -164,6 +175,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
             for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
 #pragma unroll
             for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+            s *= scale;
             if (j < j1) {
                 if (sub == 0) sc[j - j0] = s;
                 lmax = fmaxf(lmax, s);

@@ -16,6 +16,8 @@
 //
 // v_mfma_f32_16x16x32_bf16 operand layout (lane l, i = l % 16, g = l / 16): A holds row i,
 // k = 8g..8g+7; B holds column i, the same k; the result holds column i, rows 4g..4g+3.
+#include <cstdlib>
+
 #include "d3_common.h"
 
 namespace d3 {
@@ -182,6 +184,12 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     }
 }
 
+// waves per CU a launch should at least put on the chip before it trades workgroups for larger tiles
+int min_waves_per_cu() {
+    static const int v = [] { const char* e = getenv("D3_MFMA_MIN_WAVES_PER_CU"); const int n = e ? atoi(e) : 4; return n >= 1 && n <= 16 ? n : 4; }();
+    return v;
+}
+
 template <int NT, int MODE>
 int launch_rt(const GemvArgs& a, int rt, int tiles, int waves, size_t lds, hipStream_t s) {
 #define D3_LAUNCH(RT) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE, RT>), dim3(tiles / RT), dim3(64 * waves), lds, s, a)
@@ -202,7 +210,7 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
     const int nt = a.ncols > 16 ? 2 : 1;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
-    // Most tiles per workgroup (activation reuse) that still leaves >= 6 waves per CU, within 32 KiB of
+    // Most tiles per workgroup (activation reuse) that still leaves >= 4 waves per CU, within 32 KiB of
     // LDS for the cross-wave sum; stacked matrices must not share a workgroup (rows[m] % (16 RT) == 0).
     int best_rt = 1, best_waves = 4;
     const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave
@@ -218,7 +226,7 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
         while (waves > 4 && waves > turns) waves /= 2;         // at least one turn per wave
         if (waves < 4) continue;
         best_rt = rt; best_waves = waves;
-        if ((long long)(tiles / rt) * waves >= 6LL * n_cu) break;
+        if ((long long)(tiles / rt) * waves >= (long long)min_waves_per_cu() * n_cu) break;
     }
     size_t lds = (size_t)best_waves * best_rt * sw * nt * 4 * 64 * sizeof(float);   // cross-wave sum ...
     if (lds < (size_t)best_waves * kTileBytes) lds = (size_t)best_waves * kTileBytes;    // ... or one staging tile per wave

@@ -1,5 +1,4 @@
-// Device-side body of the decode attention (see attention.hip): one (column, head, context split)
-// per call by a workgroup of NW waves, plus the merge of the splits by whichever split arrives last.
+// Device-side body of the decode attention (see attention.hip).
 #pragma once
 #include "d3_common.h"
 
@@ -32,34 +31,61 @@ template <> struct KvVec<f16_t> {
     static __device__ __forceinline__ float round(float v) { return (float)(f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
 };
 
-template <int HD, int NW>
+// Sum over each aligned group of LPR lanes, every lane of a group ending with the same bits.  Sixteen lanes
+// are one DPP row: four rotate-and-add steps on the vector ALU instead of four trips through the LDS crossbar
+// (after the step by 8 the values have period 8, after the step by 4 period 4, ..., so all lanes agree exactly).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+    if (LPR == 16) {
+        v += dpp_move<0x128>(v);           // row_ror:8
+        v += dpp_move<0x124>(v);           // row_ror:4
+        v += dpp_move<0x122>(v);           // row_ror:2
+        v += dpp_move<0x121>(v);           // row_ror:1
+    } else {
+#pragma unroll
+        for (int o = LPR / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    }
+    return v;
+}
+
+template <int HD, int NW, int G>
 struct AttnShared {
-    float red_m[NW], red_s[NW];
-    float osum[NW][HD];
+    float m[G][NW], l[G][NW];              // per wave: running max and sum of each head's scores
+    float o[G][NW][HD];                    // per wave: unnormalised output of each head
     int is_last;
 };
 
+// One (column, KV head, context split) per call by a workgroup of NW waves, for the G query heads
+// h0 .. h0+G-1 that share that KV head (G = 1: plain multi-head attention, or a group size the
+// kernel is not instantiated for, handled one query head at a time).  Every cache row of the split is
+// loaded ONCE into registers, 16 bytes per lane, and used for all G heads; K and V loads go out
+// together, in chunks of up to ITMAX * RPB rows.  Each wave keeps an online softmax per head (running
+// max, sum, unnormalised output; reductions by wave shuffles), the waves are merged through LDS, and the
+// split that arrives last (arrival counter per (column, KV head)) merges all splits.
+//
 // FUSED: the call runs inside a kernel that also produced q and the newest K/V row in this launch:
 // q and that row are read from the fp32 projection buffer with agent-scope loads (the row rounded
 // to the cache's element type, i.e. exactly what later steps will read back), and the merged
 // output is published with agent-scope stores.
-template <typename T, int HD, bool FUSED, int NW>
-__device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, int c, float* sc, AttnShared<HD, NW>& sh) {
+template <typename T, int HD, bool FUSED, int NW, int G>
+__device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0, int c, AttnShared<HD, NW, G>& sh) {
     constexpr int EPL = KvVec<T>::N;       // elements per lane per 16-byte load
     constexpr int LPR = HD / EPL;          // lanes that share one cache row
     constexpr int RPW = 64 / LPR;          // rows per wave per load
     constexpr int RPB = RPW * NW;          // rows per workgroup per load
-    constexpr int U = 4;                   // loads in flight per lane
+    constexpr int ITMAX = 8;               // loads of K (and of V) in flight per lane
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
     const int j0 = split * a.split_len;
     const int j1 = min(j0 + a.split_len, ctx);
-    const size_t pidx = ((size_t)c * a.H + h) * a.n_splits + split;
     if (j0 >= j1) return;                  // nothing of this column's context falls in this split
     const int n_live = (ctx + a.split_len - 1) / a.split_len;   // splits of this column that hold rows
-    const int n = j1 - j0;
-    const int kvh = h / (a.H / a.H_kv);
+    const int kvh = h0 / (a.H / a.H_kv);
     const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
     const T* Kb = static_cast<const T*>(a.k_cache) + head_off;
     const T* Vb = static_cast<const T*>(a.v_cache) + head_off;
@@ -67,200 +93,151 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
     // FUSED: the newest row (ctx - 1) of this column, k then v, inside the projection buffer
     const float* cur_k = a.q + (size_t)c * a.q_stride + (size_t)(a.H + kvh) * HD + sub * EPL;
     const float* cur_v = cur_k + (size_t)a.H_kv * HD;
+    // scores are kept in units of log2(e) so that every exponential is one hardware exp2
+    const float scale = 1.4426950408889634f / sqrtf((float)HD);
 
-    // q is loaded raw and first touched in the score loop, after the K/V loads have been issued
-    // (scaling it here would make those loads wait for it); 1/sqrt(hd) is applied to the scores
-    const float scale = 1.0f / sqrtf((float)HD);
-    float qv[EPL];
-    {
-        const float* qp = a.q + (size_t)c * a.q_stride + (size_t)h * HD + sub * EPL;
-        if (FUSED) {
+    float m[G], l[G], acc[G][EPL];
 #pragma unroll
-            for (int e = 0; e < EPL; ++e) qv[e] = ld_agent(qp + e);
-        } else {
+    for (int g = 0; g < G; ++g) {
+        m[g] = -INFINITY; l[g] = 0.f;
 #pragma unroll
-            for (int e = 0; e < EPL; e += 4) {
-                const float4 t = *reinterpret_cast<const float4*>(qp + e);
-                qv[e] = t.x; qv[e + 1] = t.y; qv[e + 2] = t.z; qv[e + 3] = t.w;
-            }
-        }
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
     }
 
-    const int iters = (n + RPB - 1) / RPB;
-    constexpr int ITMAX = 8;               // a split of up to ITMAX * RPB rows keeps all its K and V rows in registers
-    float acc[EPL];
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[e] = 0.f;
-    float m, lsum = 0.f;
-    if (iters <= ITMAX) {
-        // short split: K and V loads all go out together (V does not wait for the softmax)
-        uint4 kv[ITMAX], vv[ITMAX];
+    const int iters = (j1 - j0 + RPB - 1) / RPB;
+    uint4 kv[ITMAX], vv[ITMAX];
+    auto issue = [&](int it0) {
 #pragma unroll
         for (int u = 0; u < ITMAX; ++u) {
-            const int j = j0 + (u * NW + wave) * RPW + rg;
+            const int j = j0 + ((it0 + u) * NW + wave) * RPW + rg;
             const int jc = j < j1 ? j : j1 - 1;
-            if (u < iters) {
+            if (it0 + u < iters) {
                 kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
                 vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
             }
         }
-        float sv[ITMAX];
-        float lmax = -INFINITY;
+    };
+    issue(0);
+    __builtin_amdgcn_sched_barrier(0);     // the first chunk's cache rows are requested before q
+    float qv[G][EPL];
 #pragma unroll
-        for (int u = 0; u < ITMAX; ++u) {
-            sv[u] = -INFINITY;
-            if (u < iters) {
-                const int j = j0 + (u * NW + wave) * RPW + rg;
-                float kf[EPL];
-                KvVec<T>::unpack(kv[u], kf);
-                if (FUSED && j == ctx - 1) {
+    for (int g = 0; g < G; ++g) {
+        const float* qp = a.q + (size_t)c * a.q_stride + (size_t)(h0 + g) * HD + sub * EPL;
+        if (FUSED) {
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
+            for (int e = 0; e < EPL; ++e) qv[g][e] = ld_agent(qp + e);
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPL; e += 4) {
+                const float4 t = *reinterpret_cast<const float4*>(qp + e);
+                qv[g][e] = t.x; qv[g][e + 1] = t.y; qv[g][e + 2] = t.z; qv[g][e + 3] = t.w;
+            }
+        }
+    }
+    for (int it0 = 0; it0 < iters; it0 += ITMAX) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float sv[ITMAX];
+            float cmax = -INFINITY;
+#pragma unroll
+            for (int u = 0; u < ITMAX; ++u) {
+                sv[u] = -INFINITY;
+                if (it0 + u < iters) {
+                    const int j = j0 + ((it0 + u) * NW + wave) * RPW + rg;
+                    float kf[EPL];
+                    KvVec<T>::unpack(kv[u], kf);
+                    if (FUSED && j == ctx - 1) {
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
+                    }
+                    float s = 0.f;
+#pragma unroll
+                    for (int e = 0; e < EPL; ++e) s = fmaf(qv[g][e], kf[e], s);
+                    s = group_sum<LPR>(s) * scale;
+                    if (j < j1) { sv[u] = s; cmax = fmaxf(cmax, s); }
                 }
-                float s = 0.f;
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
-#pragma unroll
-                for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-                s *= scale;
-                if (j < j1) { sv[u] = s; lmax = fmaxf(lmax, s); }
             }
-        }
-        lmax = wave_max(lmax);
-        if (lane == 0) sh.red_m[wave] = lmax;
-        __syncthreads();
-        m = sh.red_m[0];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) m = fmaxf(m, sh.red_m[w]);
+            for (int o = LPR; o < 64; o <<= 1) cmax = fmaxf(cmax, __shfl_xor(cmax, o, 64));   // equal within a row group already
+            const float m_new = fmaxf(m[g], cmax);          // a wave with no valid row in this chunk keeps -inf
+            if (m_new > -INFINITY) {
+                const float keep = exp2f(m[g] - m_new);       // exp2(-inf) = 0 the first time
+                l[g] *= keep;
 #pragma unroll
-        for (int u = 0; u < ITMAX; ++u) {
-            if (u < iters) {
-                const int j = j0 + (u * NW + wave) * RPW + rg;
-                const float p = expf(sv[u] - m);                    // exp(-inf) = 0 for rows past the split
-                if (sub == 0) lsum += p;
-                float vf[EPL];
-                KvVec<T>::unpack(vv[u], vf);
-                if (FUSED && j == ctx - 1) {
+                for (int e = 0; e < EPL; ++e) acc[g][e] *= keep;
 #pragma unroll
-                    for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
+                for (int u = 0; u < ITMAX; ++u) {
+                    if (it0 + u < iters) {
+                        const int j = j0 + ((it0 + u) * NW + wave) * RPW + rg;
+                        const float p = exp2f(sv[u] - m_new); // 0 for rows past the split (score -inf)
+                        if (sub == 0) l[g] += p;
+                        float vf[EPL];
+                        KvVec<T>::unpack(vv[u], vf);
+                        if (FUSED && j == ctx - 1) {
+#pragma unroll
+                            for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
+                        }
+#pragma unroll
+                        for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
+                    }
                 }
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+                m[g] = m_new;
             }
         }
-        lsum = wave_sum(lsum);
-        if (lane == 0) sh.red_s[wave] = lsum;
-    } else {
-    // ---- scores ----
-    float lmax = -INFINITY;
-    for (int it = 0; it < iters; it += U) {
-        uint4 kv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
-            const int jc = j < j1 ? j : j1 - 1;
-            kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
-            float kf[EPL];
-            KvVec<T>::unpack(kv[u], kf);
-            if (FUSED && j == ctx - 1) {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
-            }
-            float s = 0.f;
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) s = fmaf(qv[e], kf[e], s);
-#pragma unroll
-            for (int o = LPR / 2; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
-            s *= scale;
-            if (j < j1) {
-                if (sub == 0) sc[j - j0] = s;
-                lmax = fmaxf(lmax, s);
-            }
-        }
-    }
-    lmax = wave_max(lmax);
-    if (lane == 0) sh.red_m[wave] = lmax;
-    __syncthreads();
-    m = sh.red_m[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) m = fmaxf(m, sh.red_m[w]);
-
-    // ---- probabilities (relative to this split's max) ----
-    for (int t = tid; t < n; t += NW * 64) {
-        const float p = expf(sc[t] - m);
-        sc[t] = p;
-        lsum += p;
-    }
-    lsum = wave_sum(lsum);
-    if (lane == 0) sh.red_s[wave] = lsum;
-    __syncthreads();
-
-    // ---- weighted sum of V rows ----
-    for (int it = 0; it < iters; it += U) {
-        uint4 vv[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
-            const int jc = j < j1 ? j : j1 - 1;
-            vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int j = j0 + ((it + u) * NW + wave) * RPW + rg;
-            const float p = j < j1 ? sc[j - j0] : 0.f;
-            float vf[EPL];
-            KvVec<T>::unpack(vv[u], vf);
-            if (FUSED && j == ctx - 1) {
-#pragma unroll
-                for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
-            }
-#pragma unroll
-            for (int e = 0; e < EPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
-        }
-    }
-    }
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) {
-#pragma unroll
-        for (int o = LPR; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o, 64);
-    }
-    if (rg == 0) {
-#pragma unroll
-        for (int e = 0; e < EPL; ++e) sh.osum[wave][sub * EPL + e] = acc[e];
-    }
-    __syncthreads();
-    if (tid < HD) {
-        float o = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) o += sh.osum[w][tid];
-        st_agent(&a.part_o[pidx * HD + tid], o);
-    }
-    if (tid == 0) {
-        float l = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) l += sh.red_s[w];
-        st_agent(&a.part_ml[pidx * 2], m);
-        st_agent(&a.part_ml[pidx * 2 + 1], l);
+        if (it0 + ITMAX < iters) issue(it0 + ITMAX);
     }
 
-    // ---- the split that arrives last merges all splits of this (column, head) ----
-    wait_stores();                                     // this split's partial has reached the coherence point
+    // ---- waves -> LDS ----
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) {
+#pragma unroll
+            for (int o = LPR; o < 64; o <<= 1) acc[g][e] += __shfl_xor(acc[g][e], o, 64);
+        }
+        const float lw = wave_sum(l[g]);
+        if (rg == 0) {
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) sh.o[g][wave][sub * EPL + e] = acc[g][e];
+        }
+        if (lane == 0) { sh.m[g][wave] = m[g]; sh.l[g][wave] = lw; }
+    }
+    __syncthreads();
+
+    // ---- merge the waves; publish this split's partial of every head ----
+    for (int idx = tid; idx < G * HD; idx += NW * 64) {
+        const int g = idx / HD, t = idx % HD;
+        float M = sh.m[g][0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sh.m[g][w]);
+        float L = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = sh.m[g][w] > -INFINITY ? exp2f(sh.m[g][w] - M) : 0.f;
+            L += sh.l[g][w] * f;
+            o += sh.o[g][w][t] * f;
+        }
+        const size_t pidx = ((size_t)c * a.H + h0 + g) * a.n_splits + split;
+        st_agent(&a.part_o[pidx * HD + t], o);
+        if (t == 0) { st_agent(&a.part_ml[pidx * 2], M); st_agent(&a.part_ml[pidx * 2 + 1], L); }
+    }
+
+    // ---- the split that arrives last merges all splits of this (column, KV head) ----
+    wait_stores();                                     // this split's partials have reached the coherence point
     __syncthreads();
     if (tid == 0) {
-        const int done = atomicAdd(&a.tickets[c * a.H + h], 1);
+        int* ticket = &a.tickets[c * a.H + h0];          // one counter per head group, indexed by its first query head
+        const int done = atomicAdd(ticket, 1);
         sh.is_last = done == n_live - 1;
-        if (sh.is_last) __hip_atomic_store(&a.tickets[c * a.H + h], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
+        if (sh.is_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
     }
     __syncthreads();
     if (!sh.is_last) return;
-    if (tid < HD) {
+    for (int idx = tid; idx < G * HD; idx += NW * 64) {
+        const int g = idx / HD, t = idx % HD;
         // all partials are fetched in rounds of 8 splits (one round trip each), merged with a running max
-        const size_t p0 = ((size_t)c * a.H + h) * a.n_splits;
-        float gm = -INFINITY, l = 0.f, o = 0.f;
+        const size_t p0 = ((size_t)c * a.H + h0 + g) * a.n_splits;
+        float gm = -INFINITY, L = 0.f, o = 0.f;
         for (int s0 = 0; s0 < n_live; s0 += 8) {
             float ms[8], ls[8], os[8];
 #pragma unroll
@@ -268,25 +245,25 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h, 
                 const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
                 ms[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
                 ls[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
-                os[k] = ld_agent(&a.part_o[(p0 + sidx) * HD + tid]);
+                os[k] = ld_agent(&a.part_o[(p0 + sidx) * HD + t]);
             }
             float rm = gm;
 #pragma unroll
             for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[k]);
-            const float keep = expf(gm - rm);             // gm = -inf on the first round: exp(-inf) = 0
-            l *= keep; o *= keep;
+            const float keep = exp2f(gm - rm);            // gm = -inf on the first round: exp2(-inf) = 0
+            L *= keep; o *= keep;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 if (s0 + k < n_live) {
-                    const float w = expf(ms[k] - rm);
-                    l += ls[k] * w;
+                    const float w = exp2f(ms[k] - rm);
+                    L += ls[k] * w;
                     o += os[k] * w;
                 }
             }
             gm = rm;
         }
-        const float r = o / l;
-        const size_t oi = (size_t)c * a.H * HD + (size_t)h * HD + tid;
+        const float r = o / L;
+        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
         if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
         if (a.out_hi) {
             const uint32_t hb = f32_to_bf16(r);

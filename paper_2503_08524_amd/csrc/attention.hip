@@ -3,38 +3,42 @@
 // by different workgroups (each keeps a running max / sum / unnormalised output), and a
 // split that finishes last merges them (an arrival counter per (column, head)).  K and V rows
 // are streamed straight from HBM,
-// 16 bytes per lane, several rows per wave per load; the scores of a split live in LDS;
-// all reductions are wave shuffles plus one LDS hop across the four waves.
+// 16 bytes per lane, several rows per wave per load, once for all query heads of a KV head;
+// every wave keeps an online softmax per head in registers; reductions are wave shuffles plus
+// one LDS hop across the four waves.
 #include "attention.h"
 
 namespace d3 {
 
 namespace {
 
+// grid: (split, KV-head group, column); G query heads per group
+template <typename T, int HD, int G>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
+    __shared__ AttnShared<HD, 4, G> sh;
+    attn_split<T, HD, false, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
+}
+
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
-    extern __shared__ float sc[];          // scores, then probabilities, of this split
-    __shared__ AttnShared<HD, 4> sh;
-    attn_split<T, HD, false, 4>(a, blockIdx.x, blockIdx.y, blockIdx.z, sc, sh);
+int launch_g(const AttnArgs& a, hipStream_t s) {
+    const int group = a.H / a.H_kv;
+    const int g = (group == 2 || group == 4 || group == 8) ? group : 1;    // other group sizes: one query head per workgroup
+    dim3 grid(a.n_splits, a.H / g, a.ncols);
+    if (g == 8) hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, dim3(256), 0, s, a);
+    else if (g == 4) hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, dim3(256), 0, s, a);
+    else if (g == 2) hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, dim3(256), 0, s, a);
+    return (int)hipGetLastError();
 }
 
 }  // namespace
 
 // Requirements (checked by the caller): hd in {64, 128}; split_len * n_splits >= longest context;
-// n_splits <= kMaxSplits; split_len * 4 bytes of LDS <= 48 KiB.
+// n_splits <= kMaxSplits; tickets zero on entry (the kernel leaves them zero).
 int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s) {
-    dim3 grid(a.n_splits, a.H, a.ncols);
-    const size_t lds = (size_t)a.split_len * sizeof(float);
-#define D3_ATTN(T)                                                                                      \
-    do {                                                                                                \
-        if (a.hd == 64) hipLaunchKernelGGL((attn_partial_kernel<T, 64>), grid, dim3(256), lds, s, a);   \
-        else hipLaunchKernelGGL((attn_partial_kernel<T, 128>), grid, dim3(256), lds, s, a);             \
-    } while (0)
-    if (kv_dtype == 0) D3_ATTN(float);
-    else if (kv_dtype == 1) D3_ATTN(bf16_t);
-    else D3_ATTN(f16_t);
-#undef D3_ATTN
-    return (int)hipGetLastError();
+    if (kv_dtype == 0) return a.hd == 64 ? launch_g<float, 64>(a, s) : launch_g<float, 128>(a, s);
+    if (kv_dtype == 1) return a.hd == 64 ? launch_g<bf16_t, 64>(a, s) : launch_g<bf16_t, 128>(a, s);
+    return a.hd == 64 ? launch_g<f16_t, 64>(a, s) : launch_g<f16_t, 128>(a, s);
 }
 
 }  // namespace d3

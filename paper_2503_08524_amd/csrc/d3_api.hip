@@ -267,7 +267,9 @@ struct HeadOut {       // what to do after the last block
 
 // Attention split geometry for a pass whose longest context is `ctx` rows.
 void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split_len, int* n_splits) {
-    const int heads = ncols * c->desc.n_heads;
+    // workgroups per split: one per (column, KV head) when the group size has a grouped kernel, else per query head
+    const int group = c->desc.n_heads / c->desc.n_kv_heads;
+    const int heads = ncols * ((group == 2 || group == 4 || group == 8) ? c->desc.n_kv_heads : c->desc.n_heads);
     int want = (target_wgs + heads - 1) / heads;
     if (want < 1) want = 1;
     if (want > kMaxSplits) want = kMaxSplits;

@@ -88,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
     extern __shared__ float4 lds[];                     // activations of the current projection / attention scores
     __shared__ float rinv_s[1];
     __shared__ GemvEpBuf<1> ep[kCW];
-    __shared__ AttnShared<128, kWavesAll> ash;
+    __shared__ AttnShared<128, kWavesAll, 1> ash;
     __shared__ WgSync wsync;
     constexpr int HD = 128;
 
@@ -213,7 +213,7 @@ __global__ __launch_bounds__(kThreads) void decode_mega_kernel(MegaArgs m) {
         at.k_cache = qkv.k_cache; at.v_cache = qkv.v_cache;
         st.mark();
         for (int item = wg; item < m.H * m.n_splits; item += n_wg) {
-            attn_split<T, HD, true, kWavesAll>(at, item % m.n_splits, item / m.n_splits, 0, reinterpret_cast<float*>(lds), ash);
+            attn_split<T, HD, true, kWavesAll, 1>(at, item % m.n_splits, item / m.n_splits, 0, ash);
             __syncthreads();
         }
         st.mark();

@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, gemm_part, gemm_tickets, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -80,6 +80,8 @@ Layout make_layout(const d3_model_desc& d) {
     l.layer_table = take((size_t)kMaxPlanSteps * d.n_layers * 4);
     l.layer_ptrs = take((size_t)d.n_layers * sizeof(d3_layer_weights));
     l.barrier = take(512 * 4);
+    l.gemm_part = take(kGemmPartBytes);
+    l.gemm_tickets = take((size_t)kGemmTickets * 4);
     l.cand_val = take(4096 * 4);
     l.cand_idx = take(4096 * 4);
     l.total = o;
@@ -212,6 +214,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kMaxCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
+    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.gemm_tickets), 0, (size_t)kGemmTickets * sizeof(int));
     if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
     return D3_OK;
@@ -297,6 +300,8 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
 
     float2* rope_cs = c->at<float2>(c->lay.rope_cs);
+    float* gemm_part = c->at<float>(c->lay.gemm_part);
+    int* gemm_tickets = c->at<int>(c->lay.gemm_tickets);
     D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, s));
     auto dump = [&](int slot) -> int {
         if (!hidden_dump) return 0;
@@ -329,6 +334,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         const d3_layer_weights& w = c->layers[l];
         // --- attention half: x += Wo . attention(RoPE(Wq a), cache) with a = RMSNorm(x) ---
         GemvArgs g{};
+        g.splitk_part = gemm_part; g.splitk_tickets = gemm_tickets;
         g.K = dm; g.eps = d.rms_eps;
         g.w[0] = w.wq; g.w[1] = w.wk; g.w[2] = w.wv;
         g.rows[0] = qdim; g.rows[1] = kvdim; g.rows[2] = kvdim; g.total_rows = qkv_dim;
@@ -366,6 +372,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         }
 
         GemvArgs o{};
+        o.splitk_part = gemm_part; o.splitk_tickets = gemm_tickets;
         o.K = qdim; o.w[0] = w.wo; o.rows[0] = dm; o.total_rows = dm; o.out = x; o.out_stride = dm; o.ncols = ncols;
         {
             Timed t(c, D3_K_OPROJ, s);
@@ -375,9 +382,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
 
         // --- SwiGLU half: x += Wd (silu(Wg m) * (Wu m)) with m = RMSNorm(x) ---
         GemvArgs u{};
+        u.splitk_part = gemm_part; u.splitk_tickets = gemm_tickets;
         u.K = dm; u.eps = d.rms_eps; u.w[0] = w.w_gate; u.w[1] = w.w_up; u.rows[0] = F; u.rows[1] = F; u.total_rows = F;
         u.out_stride = F; u.ncols = ncols;
         GemvArgs dn{};
+        dn.splitk_part = gemm_part; dn.splitk_tickets = gemm_tickets;
         dn.K = F; dn.w[0] = w.w_down; dn.rows[0] = dm; dn.total_rows = dm; dn.out = x; dn.out_stride = dm; dn.ncols = ncols;
         if (mfma) {
             D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.mlp_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
@@ -398,6 +407,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
 
     if (head) {
         GemvArgs g{};
+        g.splitk_part = gemm_part; g.splitk_tickets = gemm_tickets;
         g.K = dm; g.eps = d.rms_eps; g.w[0] = c->lm_head; g.rows[0] = d.vocab; g.total_rows = d.vocab;
         g.out = head->logits; g.out_stride = d.vocab; g.ncols = head->n_cols;
         if (mfma) {

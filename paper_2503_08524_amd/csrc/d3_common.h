@@ -9,6 +9,8 @@ namespace d3 {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per forward pass
 constexpr int kMaxSplits = 32;     // context splits of one attention head
+constexpr size_t kGemmPartBytes = 16u << 20;   // partial tiles of a K-sliced MFMA projection
+constexpr int kGemmTickets = 4096;             // row groups a K-sliced MFMA projection may have
 
 typedef uint16_t bf16_t;           // bf16 bit pattern
 typedef _Float16 f16_t;            // IEEE half (KV cache only)
@@ -90,6 +92,9 @@ struct GemvArgs {
     ColMap cm;
     int col0;                // pass column of this launch's column 0
     int H, H_kv, hd, max_seq, kv_dtype;
+    // MFMA path, K cut into slices: partial tiles and one arrival counter per row group (zero between launches)
+    float* splitk_part;
+    int* splitk_tickets;
     unsigned long long* debug_ts;   // optional: per-workgroup 100 MHz timestamps (entry, staged, done)
     int head_start;                 // pause (units of 512 clocks) between issuing the activation loads and the weight preload
 };

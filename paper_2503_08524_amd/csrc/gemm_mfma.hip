@@ -12,7 +12,9 @@
 // flight while the current turn's MFMAs run.  Partial tiles are summed
 // through LDS.  Activations arrive pre-split as x = hi + lo (two bf16 halves, ~16 mantissa
 // bits): two MFMAs per weight tile keep fp32-like accuracy, and the matrix cores have an
-// order of magnitude of headroom on this HBM-bound contraction.
+// order of magnitude of headroom on this HBM-bound contraction.  With at most 8 columns the two halves
+// share ONE B tile (columns 0..7 hi, 8..15 lo) and their results are added in the epilogue: half the
+// activation traffic, LDS re-shaping and MFMAs.
 //
 // v_mfma_f32_16x16x32_bf16 operand layout (lane l, i = l % 16, g = l / 16): A holds row i,
 // k = 8g..8g+7; B holds column i, the same k; the result holds column i, rows 4g..4g+3.
@@ -54,6 +56,18 @@ __device__ __forceinline__ void tile_load_cached(TileRegs& r, const bf16_t* row0
         r.q[q] = u32x4{v.x, v.y, v.z, v.w};
     }
 }
+// the packed B tile of up to 8 columns: tile rows 0..7 are the hi halves of columns 0..7, rows 8..15 their lo halves
+__device__ __forceinline__ void tile_load_packed(TileRegs& r, const bf16_t* hi_k0, const bf16_t* lo_k0, size_t row_stride, int k0, int K) {
+    const int lane = threadIdx.x & 63;
+    int k = k0 + (lane & 15) * 8;
+    k = k <= K - 8 ? k : K - 8;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const bf16_t* base = q < 2 ? hi_k0 : lo_k0;
+        const uint4 v = *reinterpret_cast<const uint4*>(base + (size_t)(4 * (q & 1) + (lane >> 4)) * row_stride + (k - k0));
+        r.q[q] = u32x4{v.x, v.y, v.z, v.w};
+    }
+}
 __device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32x4 (&frag)[U]) {
     const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -66,11 +80,11 @@ __device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32
     __builtin_amdgcn_wave_barrier();
 }
 
-template <int NT, int MODE, int RT>
+template <int NT, int MODE, int RT, bool PACK>
 __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 waves
     constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;  // weight matrices per output tile
     constexpr int NA = RT * SW;                        // A tiles per wave
-    constexpr int NB = 2 * NT;                         // B tiles per wave and turn (hi and lo of each column tile)
+    constexpr int NB = PACK ? 1 : 2 * NT;              // B tiles per wave and turn (hi and lo of each column tile, or one packed tile)
     constexpr int ACC = NA * NT * 4;                   // accumulator floats per lane
     extern __shared__ float red[];                     // [waves][ACC][64] for the final sum; first, one staging tile per wave
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
@@ -101,10 +115,14 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     TileRegs ga[NA], gb[NB];                           // the loads of one turn, in flight while the previous turn computes
     auto issue = [&](int ks0) {
         const int k0 = ks0 * 32;
+        if constexpr (PACK) {
+            tile_load_packed(gb[0], a.x_hi + k0, a.x_lo + k0, a.x_stride, k0, K);
+        } else {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
-            tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
+            for (int t = 0; t < NT; ++t) {
+                tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
+                tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k0, a.x_stride, k0, K);
+            }
         }
 #pragma unroll
         for (int r = 0; r < NA; ++r) tile_load(ga[r], wrow[r] + k0, K, k0, K);
@@ -113,12 +131,17 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     auto turn = [&](int ks0, bool next, int ks_next) {
         u32x4 bf[NB][U];
         const int k1 = ks_next * 32;
+        if constexpr (PACK) {
+            tile_to_frags(gb[0], tile, bf[0]);
+            if (next) tile_load_packed(gb[0], a.x_hi + k1, a.x_lo + k1, a.x_stride, k1, K);
+        } else {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            tile_to_frags(gb[2 * t], tile, bf[2 * t]);
-            if (next) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
-            tile_to_frags(gb[2 * t + 1], tile, bf[2 * t + 1]);
-            if (next) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+            for (int t = 0; t < NT; ++t) {
+                tile_to_frags(gb[2 * t], tile, bf[2 * t]);
+                if (next) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+                tile_to_frags(gb[2 * t + 1], tile, bf[2 * t + 1]);
+                if (next) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+            }
         }
 #pragma unroll
         for (int r = 0; r < NA; ++r) {
@@ -129,8 +152,10 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
             for (int u = 0; u < U; ++u) {
                 if (ks0 + u < nks) {
                     const bf16x8 wa = __builtin_bit_cast(bf16x8, af[u]);
+                    if constexpr (PACK)
+                        acc[r][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bf[0][u]), acc[r][0], 0, 0, 0);
 #pragma unroll
-                    for (int t = 0; t < NT; ++t) {
+                    for (int t = 0; t < (PACK ? 0 : NT); ++t) {
                         acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bf[2 * t][u]), acc[r][t], 0, 0, 0);
                         acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bf[2 * t + 1][u]), acc[r][t], 0, 0, 0);
                     }
@@ -163,13 +188,17 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
         const int oi_ = idx >> 6, l = idx & 63;
         const int r = oi_ / (NT * 4), t = (oi_ >> 2) % NT, e = oi_ & 3;
         const int a0 = ((r * SW) * NT + t) * 4 + e;     // accumulator slot of the (gate) tile
+        const int row = row0 + r * 16 + 4 * (l >> 4) + e, col = t * 16 + (l & 15);
+        if (col >= a.ncols) continue;
         float s0 = 0.f, s1 = 0.f;
         for (int w = 0; w < n_waves; ++w) {
             s0 += red[((size_t)w * ACC + a0) * 64 + l];
             if (MODE == MODE_SWIGLU) s1 += red[((size_t)w * ACC + a0 + NT * 4) * 64 + l];
+            if (PACK) {                                 // the lo halves sit eight columns further
+                s0 += red[((size_t)w * ACC + a0) * 64 + l + 8];
+                if (MODE == MODE_SWIGLU) s1 += red[((size_t)w * ACC + a0 + NT * 4) * 64 + l + 8];
+            }
         }
-        const int row = row0 + r * 16 + 4 * (l >> 4) + e, col = t * 16 + (l & 15);
-        if (col >= a.ncols) continue;
         const size_t oi = (size_t)col * a.out_stride + row;
         float v;
         if (MODE == MODE_STORE) v = s0;
@@ -184,20 +213,28 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     }
 }
 
-// waves per CU a launch should at least put on the chip before it trades workgroups for larger tiles
-int min_waves_per_cu() {
-    static const int v = [] { const char* e = getenv("D3_MFMA_MIN_WAVES_PER_CU"); const int n = e ? atoi(e) : 4; return n >= 1 && n <= 16 ? n : 4; }();
-    return v;
+int env_int(const char* name, int lo, int hi) {
+    const char* e = getenv(name);
+    if (!e) return 0;
+    const int v = atoi(e);
+    return v >= lo && v <= hi ? v : 0;
 }
 
-template <int NT, int MODE>
+template <int NT, int MODE, bool PACK>
 int launch_rt(const GemvArgs& a, int rt, int tiles, int waves, size_t lds, hipStream_t s) {
-#define D3_LAUNCH(RT) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE, RT>), dim3(tiles / RT), dim3(64 * waves), lds, s, a)
+#define D3_LAUNCH(RT) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE, RT, PACK>), dim3(tiles / RT), dim3(64 * waves), lds, s, a)
     if (rt == 4) { if (MODE == MODE_SWIGLU) return (int)hipErrorInvalidValue; D3_LAUNCH((MODE == MODE_SWIGLU ? 2 : 4)); }
     else if (rt == 2) D3_LAUNCH(2);
     else D3_LAUNCH(1);
 #undef D3_LAUNCH
     return (int)hipGetLastError();
+}
+
+template <int NT, bool PACK>
+int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_t lds, hipStream_t s) {
+    if (mode == MODE_STORE) return launch_rt<NT, MODE_STORE, PACK>(a, rt, tiles, waves, lds, s);
+    if (mode == MODE_RESID) return launch_rt<NT, MODE_RESID, PACK>(a, rt, tiles, waves, lds, s);
+    return launch_rt<NT, MODE_SWIGLU, PACK>(a, rt, tiles, waves, lds, s);
 }
 
 }  // namespace
@@ -210,10 +247,15 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
     const int nt = a.ncols > 16 ? 2 : 1;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
-    // Most tiles per workgroup (activation reuse) that still leaves >= 4 waves per CU, within 32 KiB of
-    // LDS for the cross-wave sum; stacked matrices must not share a workgroup (rows[m] % (16 RT) == 0).
+    const bool pack = a.ncols <= 8;
+    const int nb = pack ? 1 : 2 * nt;
+    // Most tiles per workgroup (activation reuse) that still puts a workgroup on at least 0.6 of the compute units
+    // (measured: fewer starve the memory system, more only add activation traffic) and >= 4 waves per CU on the
+    // chip, within the register budget; stacked matrices must not share a workgroup
+    // (rows[m] % (16 RT) == 0).
     int best_rt = 1, best_waves = 4;
     const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave
+    const int rt_forced = env_int("D3_MFMA_RT", 1, 4), waves_forced = env_int("D3_MFMA_WAVES", 1, 8);
     for (int rt = rt_max; rt >= 1; rt /= 2) {
         if (tiles % rt != 0) continue;
         bool aligned = true;
@@ -221,23 +263,19 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
             for (int m = 0; m < 3; ++m)
                 if (a.rows[m] % (16 * rt) != 0) aligned = false;
         if (!aligned) continue;
-        int waves = 32 / (rt * nt * sw);
+        int waves = 32 / (rt * sw * (nb > 2 ? 2 : 1));
         if (waves > 8) waves = 8;
         while (waves > 4 && waves > turns) waves /= 2;         // at least one turn per wave
         if (waves < 4) continue;
+        if (waves_forced) waves = waves_forced;
         best_rt = rt; best_waves = waves;
-        if ((long long)(tiles / rt) * waves >= (long long)min_waves_per_cu() * n_cu) break;
+        if (rt_forced ? rt <= rt_forced : (10 * (tiles / rt) >= 6 * n_cu && (long long)(tiles / rt) * waves >= 4LL * n_cu)) break;
     }
     size_t lds = (size_t)best_waves * best_rt * sw * nt * 4 * 64 * sizeof(float);   // cross-wave sum ...
     if (lds < (size_t)best_waves * kTileBytes) lds = (size_t)best_waves * kTileBytes;    // ... or one staging tile per wave
-    if (nt == 1) {
-        if (mode == MODE_STORE) return launch_rt<1, MODE_STORE>(a, best_rt, tiles, best_waves, lds, s);
-        if (mode == MODE_RESID) return launch_rt<1, MODE_RESID>(a, best_rt, tiles, best_waves, lds, s);
-        return launch_rt<1, MODE_SWIGLU>(a, best_rt, tiles, best_waves, lds, s);
-    }
-    if (mode == MODE_STORE) return launch_rt<2, MODE_STORE>(a, best_rt, tiles, best_waves, lds, s);
-    if (mode == MODE_RESID) return launch_rt<2, MODE_RESID>(a, best_rt, tiles, best_waves, lds, s);
-    return launch_rt<2, MODE_SWIGLU>(a, best_rt, tiles, best_waves, lds, s);
+    if (nt == 2) return launch_mode<2, false>(a, mode, best_rt, tiles, best_waves, lds, s);
+    if (pack) return launch_mode<1, true>(a, mode, best_rt, tiles, best_waves, lds, s);
+    return launch_mode<1, false>(a, mode, best_rt, tiles, best_waves, lds, s);
 }
 
 }  // namespace d3

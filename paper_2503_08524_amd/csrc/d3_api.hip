@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, gemm_part, gemm_tickets, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -80,8 +80,9 @@ Layout make_layout(const d3_model_desc& d) {
     l.layer_table = take((size_t)kMaxPlanSteps * d.n_layers * 4);
     l.layer_ptrs = take((size_t)d.n_layers * sizeof(d3_layer_weights));
     l.barrier = take(512 * 4);
-    l.gemm_part = take(kGemmPartBytes);
-    l.gemm_tickets = take((size_t)kGemmTickets * 4);
+    l.n_hi = take(C * d.d_model * 2);
+    l.n_lo = take(C * d.d_model * 2);
+    l.ssq = take(C * kSsqStride * 4);
     l.cand_val = take(4096 * 4);
     l.cand_idx = take(4096 * 4);
     l.total = o;
@@ -214,7 +215,6 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kMaxCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
-    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.gemm_tickets), 0, (size_t)kGemmTickets * sizeof(int));
     if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
     return D3_OK;
@@ -300,8 +300,9 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
 
     float2* rope_cs = c->at<float2>(c->lay.rope_cs);
-    float* gemm_part = c->at<float>(c->lay.gemm_part);
-    int* gemm_tickets = c->at<int>(c->lay.gemm_tickets);
+    bf16_t *n_hi = c->at<bf16_t>(c->lay.n_hi), *n_lo = c->at<bf16_t>(c->lay.n_lo);   // split of residual * next norm's gain
+    float* ssq = c->at<float>(c->lay.ssq);
+    int ssq_parts = 1;
     D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, s));
     auto dump = [&](int slot) -> int {
         if (!hidden_dump) return 0;
@@ -329,12 +330,19 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     int split_len, n_splits;
     pick_splits(c, ncols, cm.pos(ncols - 1) + 1, 2 * c->n_cu, &split_len, &n_splits);
 
+    // Matrix-core path: RMSNorm lives inside the projections.  Whoever writes the residual also writes the split of
+    // residual * (gain of the norm that reads it next) and partial sums of squares; the reading projection scales its
+    // sums by 1/rms.  The norm after block e is the next executed block's, or the final one.
+    auto gain_after = [&](int e) -> const float* {
+        return static_cast<const float*>(e + 1 < n_ids ? c->layers[ids[e + 1]].attn_norm : c->final_norm);
+    };
+    if (mfma) D3_HIP(launch_gain_split(x, dm, gain_after(-1), dm, ncols, n_hi, n_lo, ssq, s));
+
     for (int e = 0; e < n_ids; ++e) {
         const int l = ids[e];
         const d3_layer_weights& w = c->layers[l];
         // --- attention half: x += Wo . attention(RoPE(Wq a), cache) with a = RMSNorm(x) ---
         GemvArgs g{};
-        g.splitk_part = gemm_part; g.splitk_tickets = gemm_tickets;
         g.K = dm; g.eps = d.rms_eps;
         g.w[0] = w.wq; g.w[1] = w.wk; g.w[2] = w.wv;
         g.rows[0] = qdim; g.rows[1] = kvdim; g.rows[2] = kvdim; g.total_rows = qkv_dim;
@@ -342,8 +350,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         void* k_layer = c->k_cache + (size_t)l * c->kv_layer_bytes();
         void* v_layer = c->v_cache + (size_t)l * c->kv_layer_bytes();
         if (mfma) {
-            D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.attn_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
-            g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            g.x_hi = n_hi; g.x_lo = n_lo; g.x_stride = dm; g.ssq_in = ssq; g.ssq_parts = ssq_parts;
             {
                 Timed t(c, D3_K_QKV, s);
                 D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
@@ -372,28 +379,30 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         }
 
         GemvArgs o{};
-        o.splitk_part = gemm_part; o.splitk_tickets = gemm_tickets;
         o.K = qdim; o.w[0] = w.wo; o.rows[0] = dm; o.total_rows = dm; o.out = x; o.out_stride = dm; o.ncols = ncols;
         {
             Timed t(c, D3_K_OPROJ, s);
-            if (mfma) { o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim; D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s)); }
+            if (mfma) {
+                o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim;
+                o.out_hi = n_hi; o.out_lo = n_lo; o.gain_next = static_cast<const float*>(w.mlp_norm); o.ssq_out = ssq;
+                D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s, &ssq_parts));
+            }
             else { o.x = attn_o; o.x_stride = qdim; D3_HIP(alu(o, 0, ncols, MODE_RESID, false)); }
         }
 
         // --- SwiGLU half: x += Wd (silu(Wg m) * (Wu m)) with m = RMSNorm(x) ---
         GemvArgs u{};
-        u.splitk_part = gemm_part; u.splitk_tickets = gemm_tickets;
         u.K = dm; u.eps = d.rms_eps; u.w[0] = w.w_gate; u.w[1] = w.w_up; u.rows[0] = F; u.rows[1] = F; u.total_rows = F;
         u.out_stride = F; u.ncols = ncols;
         GemvArgs dn{};
-        dn.splitk_part = gemm_part; dn.splitk_tickets = gemm_tickets;
         dn.K = F; dn.w[0] = w.w_down; dn.rows[0] = dm; dn.total_rows = dm; dn.out = x; dn.out_stride = dm; dn.ncols = ncols;
         if (mfma) {
-            D3_HIP(launch_norm_split(x, dm, static_cast<const float*>(w.mlp_norm), d.rms_eps, dm, ncols, s_hi, s_lo, s));
-            u.x_hi = s_hi; u.x_lo = s_lo; u.x_stride = dm; u.out = nullptr; u.out_hi = f_hi; u.out_lo = f_lo;
+            u.x_hi = n_hi; u.x_lo = n_lo; u.x_stride = dm; u.ssq_in = ssq; u.ssq_parts = ssq_parts;
+            u.out = nullptr; u.out_hi = f_hi; u.out_lo = f_lo;
             { Timed t(c, D3_K_GATE_UP, s); D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, s)); }
             dn.x_hi = f_hi; dn.x_lo = f_lo; dn.x_stride = F;
-            { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s)); }
+            dn.out_hi = n_hi; dn.out_lo = n_lo; dn.gain_next = gain_after(e); dn.ssq_out = ssq;
+            { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s, &ssq_parts)); }
         } else {
             u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
             if (e == n_ids - 1) u.debug_ts = c->debug_ts;      // debug timeline of the last block's gate/up launch
@@ -407,13 +416,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
 
     if (head) {
         GemvArgs g{};
-        g.splitk_part = gemm_part; g.splitk_tickets = gemm_tickets;
         g.K = dm; g.eps = d.rms_eps; g.w[0] = c->lm_head; g.rows[0] = d.vocab; g.total_rows = d.vocab;
         g.out = head->logits; g.out_stride = d.vocab; g.ncols = head->n_cols;
         if (mfma) {
-            D3_HIP(launch_norm_split(x + (size_t)head->first_col * dm, dm, static_cast<const float*>(c->final_norm), d.rms_eps, dm,
-                                     head->n_cols, s_hi, s_lo, s));
-            g.x_hi = s_hi; g.x_lo = s_lo; g.x_stride = dm;
+            g.x_hi = n_hi + (size_t)head->first_col * dm; g.x_lo = n_lo + (size_t)head->first_col * dm; g.x_stride = dm;
+            g.ssq_in = ssq + (size_t)head->first_col * kSsqStride; g.ssq_parts = ssq_parts;
             Timed t(c, D3_K_LM_HEAD, s);
             D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
         } else {

@@ -9,8 +9,7 @@ namespace d3 {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per forward pass
 constexpr int kMaxSplits = 32;     // context splits of one attention head
-constexpr size_t kGemmPartBytes = 16u << 20;   // partial tiles of a K-sliced MFMA projection
-constexpr int kGemmTickets = 4096;             // row groups a K-sliced MFMA projection may have
+constexpr int kSsqStride = 512;    // partial sums of squares kept per column (one per workgroup of the producing projection)
 
 typedef uint16_t bf16_t;           // bf16 bit pattern
 typedef _Float16 f16_t;            // IEEE half (KV cache only)
@@ -92,21 +91,27 @@ struct GemvArgs {
     ColMap cm;
     int col0;                // pass column of this launch's column 0
     int H, H_kv, hd, max_seq, kv_dtype;
-    // MFMA path, K cut into slices: partial tiles and one arrival counter per row group (zero between launches)
-    float* splitk_part;
-    int* splitk_tickets;
+    // MFMA path, RMSNorm folded into the projections around it.  A projection whose input is a normalised
+    // residual (STORE, SWIGLU) gets x * gain pre-split in x_hi/x_lo and scales its sums by
+    // 1/sqrt(sum(ssq_in[col][0..ssq_parts)) / K + eps); a residual projection (RESID) with ssq_out set also
+    // writes the split of (new x) * gain_next to out_hi/out_lo and its workgroup's sum of squares of the new x
+    // to ssq_out[col][workgroup].
+    const float* ssq_in;     // [ncols][kSsqStride]
+    int ssq_parts;
+    float* ssq_out;          // [ncols][kSsqStride]
+    const float* gain_next;  // [total_rows]
     unsigned long long* debug_ts;   // optional: per-workgroup 100 MHz timestamps (entry, staged, done)
     int head_start;                 // pause (units of 512 clocks) between issuing the activation loads and the weight preload
 };
 
 // returns hipError_t as int
 int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, int n_wg, hipStream_t s);
-int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s);
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups = nullptr);   // n_groups: workgroups launched (= parts written to ssq_out)
 size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
 
-// RMSNorm + split into bf16 hi/lo for the MFMA path: out = x / sqrt(mean(x^2)+eps) * gain
-int launch_norm_split(const float* x, int x_stride, const float* gain, float eps, int K, int ncols,
-                      bf16_t* hi, bf16_t* lo, hipStream_t s);
+// first step of a pass on the MFMA path: hi + lo = x * gain (bf16 halves), ssq[col * kSsqStride] = sum(x^2)
+int launch_gain_split(const float* x, int x_stride, const float* gain, int K, int ncols,
+                      bf16_t* hi, bf16_t* lo, float* ssq, hipStream_t s);
 
 // ---------------- the rest of a block ----------------
 // x[c][:] = E[token(c)][:], and the pass's rotary table rope_cs[c][j] = (cos, sin)(pos(c) * inv_freq[j])

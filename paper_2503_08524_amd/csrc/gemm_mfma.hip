@@ -87,6 +87,8 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     constexpr int NB = PACK ? 1 : 2 * NT;              // B tiles per wave and turn (hi and lo of each column tile, or one packed tile)
     constexpr int ACC = NA * NT * 4;                   // accumulator floats per lane
     extern __shared__ float red[];                     // [waves][ACC][64] for the final sum; first, one staging tile per wave
+    __shared__ float inv_rms[kMaxCols];                // RMSNorm scale of each column (input side)
+    __shared__ float sq[MODE == MODE_RESID ? kMaxCols : 1][16 * RT];   // squares of the new residual (output side)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
     const int K = a.K, row0 = blockIdx.x * (16 * RT);
     char* tile = reinterpret_cast<char*>(red) + (size_t)wave * kTileBytes;
@@ -164,14 +166,37 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
         }
     };
 
+    // 16 threads add up one column's partial sums of squares, in a fixed order; the loads queue behind the first
+    // turn's weights and are consumed before it
+    auto column_scales = [&]() {
+        if (MODE == MODE_RESID || !a.ssq_in) return;
+        for (int col = tid >> 4; col < a.ncols; col += blockDim.x >> 4) {
+            const float* p = a.ssq_in + (size_t)col * kSsqStride;
+            float ss = 0.f;
+            for (int i0 = tid & 15; i0 < a.ssq_parts; i0 += 16 * 8) {
+                float t[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t[j] = i0 + 16 * j < a.ssq_parts ? p[i0 + 16 * j] : 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) ss += t[j];
+            }
+#pragma unroll
+            for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
+            if ((tid & 15) == 0) inv_rms[col] = 1.0f / sqrtf(ss / (float)K + a.eps);
+        }
+    };
+
     int ks0 = wave * U;
     if (ks0 < nks) {
         issue(ks0);
+        column_scales();
         while (ks0 + stride < nks) {                   // steady state: every register set is re-issued unconditionally
             turn(ks0, true, ks0 + stride);
             ks0 += stride;
         }
         turn(ks0, false, 0);
+    } else {
+        column_scales();
     }
     __syncthreads();                                   // the staging tiles give way to the partial sums
 
@@ -200,15 +225,30 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
             }
         }
         const size_t oi = (size_t)col * a.out_stride + row;
+        if (MODE != MODE_RESID && a.ssq_in) { s0 *= inv_rms[col]; s1 *= inv_rms[col]; }
         float v;
         if (MODE == MODE_STORE) v = s0;
         else if (MODE == MODE_RESID) v = a.out[oi] + s0;
         else v = s0 / (1.0f + expf(-s0)) * s1;
         if (a.out) a.out[oi] = v;
+        float split = v;
+        if (MODE == MODE_RESID && a.ssq_out) {         // the consumer is a normalised projection: hand it x * gain and sum(x^2)
+            sq[col][r * 16 + 4 * (l >> 4) + e] = v * v;
+            split = v * a.gain_next[row];
+        }
         if (a.out_hi) {
-            const uint32_t hb = f32_to_bf16(v);
+            const uint32_t hb = f32_to_bf16(split);
             a.out_hi[oi] = (bf16_t)hb;
-            a.out_lo[oi] = (bf16_t)f32_to_bf16(v - bf16_to_f32(hb));
+            a.out_lo[oi] = (bf16_t)f32_to_bf16(split - bf16_to_f32(hb));
+        }
+    }
+    if (MODE == MODE_RESID && a.ssq_out) {
+        __syncthreads();
+        if (tid < a.ncols) {
+            float ss = 0.f;
+#pragma unroll 4
+            for (int i = 0; i < 16 * RT; ++i) ss += sq[tid][i];
+            a.ssq_out[(size_t)tid * kSsqStride + blockIdx.x] = ss;
         }
     }
 }
@@ -241,8 +281,9 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 
 // Requirements (checked by the caller): bf16 weights; K % 32 == 0; total_rows and every rows[m]
 // multiples of 16; 1 <= ncols <= 32; x_hi/x_lo hold 32 rows of x_stride elements (rows beyond
-// ncols may hold anything finite or not: their columns are never written).
-int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
+// ncols may hold anything finite or not: their columns are never written); with ssq_out, total_rows / 16 <=
+// kSsqStride (every workgroup owns a slot).
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
@@ -271,6 +312,8 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s) {
         best_rt = rt; best_waves = waves;
         if (rt_forced ? rt <= rt_forced : (10 * (tiles / rt) >= 6 * n_cu && (long long)(tiles / rt) * waves >= 4LL * n_cu)) break;
     }
+    if (n_groups) *n_groups = tiles / best_rt;
+    if (a.ssq_out && tiles / best_rt > kSsqStride) return (int)hipErrorInvalidValue;
     size_t lds = (size_t)best_waves * best_rt * sw * nt * 4 * 64 * sizeof(float);   // cross-wave sum ...
     if (lds < (size_t)best_waves * kTileBytes) lds = (size_t)best_waves * kTileBytes;    // ... or one staging tile per wave
     if (nt == 2) return launch_mode<2, false>(a, mode, best_rt, tiles, best_waves, lds, s);

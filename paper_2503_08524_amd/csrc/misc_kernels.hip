@@ -1,4 +1,4 @@
-// Small kernels around the projections: embedding gather, RMSNorm + bf16 split for
+// Small kernels around the projections: embedding gather, gain + bf16 split for
 // the MFMA path, rotary embedding + KV append, greedy argmax, missing-state KV fill.
 #include "d3_common.h"
 
@@ -34,44 +34,24 @@ __global__ __launch_bounds__(256) void embed_kernel(const W* __restrict__ emb, c
     }
 }
 
-// ---------------- RMSNorm (optional) + split into bf16 hi/lo ----------------
-// One workgroup per column.  A thread keeps up to 8 float4 of the column in registers (all loads
-// issued together), so the column is read once; wider columns fall back to a second read.
-__global__ __launch_bounds__(256) void norm_split_kernel(const float* __restrict__ x, int x_stride,
-                                                         const float* __restrict__ gain, float eps, int K,
-                                                         bf16_t* __restrict__ hi, bf16_t* __restrict__ lo) {
+// ---------------- gain + split into bf16 hi/lo, sum of squares ----------------
+// The matrix-core projections fold the RMSNorm scale 1/rms into their epilogue; what they need from the
+// residual is hi + lo = x * gain and sum(x^2).  Inside a pass the residual projections produce both; this
+// kernel does it for the embedding output.  One workgroup per column; a thread keeps up to 8 float4 of the
+// column in registers (all loads issued together); wider columns fall back to a second read.
+__global__ __launch_bounds__(256) void gain_split_kernel(const float* __restrict__ x, int x_stride,
+                                                         const float* __restrict__ gain, int K,
+                                                         bf16_t* __restrict__ hi, bf16_t* __restrict__ lo,
+                                                         float* __restrict__ ssq) {
     constexpr int R = 8;
     __shared__ float red[4];
     const int c = blockIdx.x, tid = threadIdx.x;
     const float* xc = x + (size_t)c * x_stride;
     const int n4 = K / 4;
-    float4 v[R], g[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int i4 = tid + r * 256;
-        v[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        g[r] = make_float4(1.f, 1.f, 1.f, 1.f);
-        if (i4 < n4) {
-            v[r] = *reinterpret_cast<const float4*>(xc + i4 * 4);
-            if (gain) g[r] = *reinterpret_cast<const float4*>(gain + i4 * 4);
-        }
-    }
-    float rinv = 1.0f;
-    if (gain) {
-        float ss = 0.f;
-#pragma unroll
-        for (int r = 0; r < R; ++r) ss += v[r].x * v[r].x + v[r].y * v[r].y + v[r].z * v[r].z + v[r].w * v[r].w;
-        for (int i4 = tid + R * 256; i4 < n4; i4 += 256) {
-            const float4 t = *reinterpret_cast<const float4*>(xc + i4 * 4);
-            ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
-        }
-        ss = wave_sum(ss);
-        if ((tid & 63) == 0) red[tid >> 6] = ss;
-        __syncthreads();
-        rinv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)K + eps);
-    }
+    float ss = 0.f;
     auto emit = [&](int i4, const float4& t, const float4& gg) {
-        const float f[4] = {t.x * rinv * gg.x, t.y * rinv * gg.y, t.z * rinv * gg.z, t.w * rinv * gg.w};
+        const float f[4] = {t.x * gg.x, t.y * gg.y, t.z * gg.z, t.w * gg.w};
+        ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
         uint32_t h[4], l[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -81,16 +61,26 @@ __global__ __launch_bounds__(256) void norm_split_kernel(const float* __restrict
         *reinterpret_cast<uint2*>(hi + (size_t)c * K + i4 * 4) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
         *reinterpret_cast<uint2*>(lo + (size_t)c * K + i4 * 4) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
     };
+    float4 v[R], g[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i4 = tid + r * 256;
+        if (i4 < n4) {
+            v[r] = *reinterpret_cast<const float4*>(xc + i4 * 4);
+            g[r] = *reinterpret_cast<const float4*>(gain + i4 * 4);
+        }
+    }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int i4 = tid + r * 256;
         if (i4 < n4) emit(i4, v[r], g[r]);
     }
-    for (int i4 = tid + R * 256; i4 < n4; i4 += 256) {
-        float4 gg = make_float4(1.f, 1.f, 1.f, 1.f);
-        if (gain) gg = *reinterpret_cast<const float4*>(gain + i4 * 4);
-        emit(i4, *reinterpret_cast<const float4*>(xc + i4 * 4), gg);
-    }
+    for (int i4 = tid + R * 256; i4 < n4; i4 += 256)
+        emit(i4, *reinterpret_cast<const float4*>(xc + i4 * 4), *reinterpret_cast<const float4*>(gain + i4 * 4));
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) ssq[(size_t)c * kSsqStride] = (red[0] + red[1]) + (red[2] + red[3]);
 }
 
 // ---------------- rotary embedding + KV append ----------------
@@ -204,9 +194,9 @@ int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, C
     return (int)hipGetLastError();
 }
 
-int launch_norm_split(const float* x, int x_stride, const float* gain, float eps, int K, int ncols,
-                      bf16_t* hi, bf16_t* lo, hipStream_t s) {
-    hipLaunchKernelGGL(norm_split_kernel, dim3(ncols), dim3(256), 0, s, x, x_stride, gain, eps, K, hi, lo);
+int launch_gain_split(const float* x, int x_stride, const float* gain, int K, int ncols,
+                      bf16_t* hi, bf16_t* lo, float* ssq, hipStream_t s) {
+    hipLaunchKernelGGL(gain_split_kernel, dim3(ncols), dim3(256), 0, s, x, x_stride, gain, K, hi, lo, ssq);
     return (int)hipGetLastError();
 }
 

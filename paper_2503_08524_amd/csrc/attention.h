@@ -11,6 +11,7 @@ template <> struct KvVec<float> {
         f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
     static __device__ __forceinline__ float round(float v) { return v; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
 };
 template <> struct KvVec<bf16_t> {
     static constexpr int N = 8;
@@ -19,6 +20,7 @@ template <> struct KvVec<bf16_t> {
         f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
     }
     static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
 };
 template <> struct KvVec<f16_t> {
     static constexpr int N = 8;
@@ -29,6 +31,7 @@ template <> struct KvVec<f16_t> {
         for (int e = 0; e < 8; ++e) f[e] = (float)h[e];
     }
     static __device__ __forceinline__ float round(float v) { return (float)(f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
+    static __device__ __forceinline__ void store(f16_t* p, float v) { *p = (f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
 };
 
 // Sum over each aligned group of LPR lanes, every lane of a group ending with the same bits.  Sixteen lanes
@@ -71,7 +74,13 @@ struct AttnShared {
 // q and that row are read from the fp32 projection buffer with agent-scope loads (the row rounded
 // to the cache's element type, i.e. exactly what later steps will read back), and the merged
 // output is published with agent-scope stores.
-template <typename T, int HD, bool FUSED, int NW, int G>
+//
+// ROPE: q and the newest K/V row of every column arrive unrotated in the projection buffer, and that row
+// is not in the cache yet (every column of the pass is a different sequence).  The workgroup rotates q
+// while loading it (half-split pairing: dims j and j + HD/2 turn by the column's angle j), and the split
+// that holds the newest position rotates k, rounds k and v to the cache's element type, uses them and
+// appends them to the cache.
+template <typename T, int HD, bool FUSED, int NW, int G, bool ROPE = false>
 __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0, int c, AttnShared<HD, NW, G>& sh) {
     constexpr int EPL = KvVec<T>::N;       // elements per lane per 16-byte load
     constexpr int LPR = HD / EPL;          // lanes that share one cache row
@@ -82,8 +91,10 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
     const int j0 = split * a.split_len;
-    const int j1 = min(j0 + a.split_len, ctx);
-    if (j0 >= j1) return;                  // nothing of this column's context falls in this split
+    const int jend = min(j0 + a.split_len, ctx);
+    if (j0 >= jend) return;                // nothing of this column's context falls in this split
+    const bool has_new = ROPE && jend == ctx;          // ROPE: the newest position comes from the projection buffer ...
+    const int j1 = has_new ? ctx - 1 : jend;           // ... and the cache rows of this split end before it
     const int n_live = (ctx + a.split_len - 1) / a.split_len;   // splits of this column that hold rows
     const int kvh = h0 / (a.H / a.H_kv);
     const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
@@ -119,6 +130,44 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     };
     issue(0);
     __builtin_amdgcn_sched_barrier(0);     // the first chunk's cache rows are requested before q
+    // ROPE: this lane's elements sit in the lower (partner HD/2 above) or upper (partner HD/2 below) half of the head
+    const bool upper = sub * EPL >= HD / 2;
+    const int poff = upper ? -(HD / 2) : HD / 2;
+    float cosv[EPL], sinv[EPL], newk[EPL], newv[EPL];
+    auto rotate = [&](const float* own, const float* partner, float* y) {
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) y[e] = upper ? partner[e] * sinv[e] + own[e] * cosv[e] : own[e] * cosv[e] - partner[e] * sinv[e];
+    };
+    auto load_vec = [&](const float* p, float* y) {
+#pragma unroll
+        for (int e = 0; e < EPL; e += 4) {
+            const float4 t = *reinterpret_cast<const float4*>(p + e);
+            y[e] = t.x; y[e + 1] = t.y; y[e + 2] = t.z; y[e + 3] = t.w;
+        }
+    };
+    if (ROPE) {
+        const float2* cs = a.rope_cs + (size_t)c * (HD / 2) + (sub * EPL) % (HD / 2);
+#pragma unroll
+        for (int e = 0; e < EPL; e += 2) {
+            const float4 t = *reinterpret_cast<const float4*>(cs + e);
+            cosv[e] = t.x; sinv[e] = t.y; cosv[e + 1] = t.z; sinv[e + 1] = t.w;
+        }
+        if (has_new) {
+            float own[EPL], partner[EPL];
+            load_vec(cur_k, own);
+            load_vec(cur_k + poff, partner);
+            rotate(own, partner, newk);
+            load_vec(cur_v, newv);
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) { newk[e] = KvVec<T>::round(newk[e]); newv[e] = KvVec<T>::round(newv[e]); }
+            if (wave == 0 && rg == 0) {    // one copy of the row goes to the cache (the caches are this launch's to extend)
+                T* kd = const_cast<T*>(Kb) + (size_t)(ctx - 1) * HD + sub * EPL;
+                T* vd = const_cast<T*>(Vb) + (size_t)(ctx - 1) * HD + sub * EPL;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) { KvVec<T>::store(kd + e, newk[e]); KvVec<T>::store(vd + e, newv[e]); }
+            }
+        }
+    }
     float qv[G][EPL];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -131,6 +180,27 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
             for (int e = 0; e < EPL; e += 4) {
                 const float4 t = *reinterpret_cast<const float4*>(qp + e);
                 qv[g][e] = t.x; qv[g][e + 1] = t.y; qv[g][e + 2] = t.z; qv[g][e + 3] = t.w;
+            }
+            if (ROPE) {
+                float partner[EPL], y[EPL];
+                load_vec(qp + poff, partner);
+                rotate(qv[g], partner, y);
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) qv[g][e] = y[e];
+            }
+        }
+    }
+    if (has_new && wave == 0) {            // the newest row opens wave 0's running softmax: weight 1 at its own score
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float sn = 0.f;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) sn = fmaf(qv[g][e], newk[e], sn);
+            m[g] = group_sum<LPR>(sn) * scale;         // every row group holds the same q and k: the same score in all lanes
+            if (rg == 0) {
+                if (sub == 0) l[g] = 1.f;
+#pragma unroll
+                for (int e = 0; e < EPL; ++e) acc[g][e] = newv[e];
             }
         }
     }
@@ -150,6 +220,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
 #pragma unroll
                         for (int e = 0; e < EPL; ++e) kf[e] = KvVec<T>::round(ld_agent(cur_k + e));
                     }
+
                     float s = 0.f;
 #pragma unroll
                     for (int e = 0; e < EPL; ++e) s = fmaf(qv[g][e], kf[e], s);
@@ -177,6 +248,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
 #pragma unroll
                             for (int e = 0; e < EPL; ++e) vf[e] = KvVec<T>::round(ld_agent(cur_v + e));
                         }
+
 #pragma unroll
                         for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p, vf[e], acc[g][e]);
                     }

@@ -13,21 +13,21 @@ namespace d3 {
 namespace {
 
 // grid: (split, KV-head group, column); G query heads per group
-template <typename T, int HD, int G>
+template <typename T, int HD, int G, bool ROPE>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     __shared__ AttnShared<HD, 4, G> sh;
-    attn_split<T, HD, false, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
+    attn_split<T, HD, false, 4, G, ROPE>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
 }
 
-template <typename T, int HD>
+template <typename T, int HD, bool ROPE>
 int launch_g(const AttnArgs& a, hipStream_t s) {
     const int group = a.H / a.H_kv;
     const int g = (group == 2 || group == 4 || group == 8) ? group : 1;    // other group sizes: one query head per workgroup
     dim3 grid(a.n_splits, a.H / g, a.ncols);
-    if (g == 8) hipLaunchKernelGGL((attn_kernel<T, HD, 8>), grid, dim3(256), 0, s, a);
-    else if (g == 4) hipLaunchKernelGGL((attn_kernel<T, HD, 4>), grid, dim3(256), 0, s, a);
-    else if (g == 2) hipLaunchKernelGGL((attn_kernel<T, HD, 2>), grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL((attn_kernel<T, HD, 1>), grid, dim3(256), 0, s, a);
+    if (g == 8) hipLaunchKernelGGL((attn_kernel<T, HD, 8, ROPE>), grid, dim3(256), 0, s, a);
+    else if (g == 4) hipLaunchKernelGGL((attn_kernel<T, HD, 4, ROPE>), grid, dim3(256), 0, s, a);
+    else if (g == 2) hipLaunchKernelGGL((attn_kernel<T, HD, 2, ROPE>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((attn_kernel<T, HD, 1, ROPE>), grid, dim3(256), 0, s, a);
     return (int)hipGetLastError();
 }
 
@@ -35,10 +35,17 @@ int launch_g(const AttnArgs& a, hipStream_t s) {
 
 // Requirements (checked by the caller): hd in {64, 128}; split_len * n_splits >= longest context;
 // n_splits <= kMaxSplits; tickets zero on entry (the kernel leaves them zero).
+template <bool ROPE>
+int launch_t(const AttnArgs& a, int kv_dtype, hipStream_t s) {
+    if (kv_dtype == 0) return a.hd == 64 ? launch_g<float, 64, ROPE>(a, s) : launch_g<float, 128, ROPE>(a, s);
+    if (kv_dtype == 1) return a.hd == 64 ? launch_g<bf16_t, 64, ROPE>(a, s) : launch_g<bf16_t, 128, ROPE>(a, s);
+    return a.hd == 64 ? launch_g<f16_t, 64, ROPE>(a, s) : launch_g<f16_t, 128, ROPE>(a, s);
+}
+
+// With rope_cs set, q and the newest K/V row of each column are still unrotated in the projection buffer and
+// the kernel rotates and appends them itself; the columns of such a pass must belong to different sequences.
 int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s) {
-    if (kv_dtype == 0) return a.hd == 64 ? launch_g<float, 64>(a, s) : launch_g<float, 128>(a, s);
-    if (kv_dtype == 1) return a.hd == 64 ? launch_g<bf16_t, 64>(a, s) : launch_g<bf16_t, 128>(a, s);
-    return a.hd == 64 ? launch_g<f16_t, 64>(a, s) : launch_g<f16_t, 128>(a, s);
+    return a.rope_cs ? launch_t<true>(a, kv_dtype, s) : launch_t<false>(a, kv_dtype, s);
 }
 
 }  // namespace d3

@@ -298,6 +298,10 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     bf16_t *f_hi = c->at<bf16_t>(c->lay.f_hi), *f_lo = c->at<bf16_t>(c->lay.f_lo);
     const bool mfma = c->mfma_ok && (ncols >= 2 || !c->alu_ok);
     const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
+    // a decode pass (every column a different sequence) on the matrix-core path leaves the rotary embedding and the
+    // cache append to the attention kernel; a prompt chunk holds several positions of one sequence and needs the
+    // rows in the cache before attention starts
+    const bool rope_in_attn = mfma && ncols <= cm.B;
 
     float2* rope_cs = c->at<float2>(c->lay.rope_cs);
     bf16_t *n_hi = c->at<bf16_t>(c->lay.n_hi), *n_lo = c->at<bf16_t>(c->lay.n_lo);   // split of residual * next norm's gain
@@ -355,10 +359,12 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
                 Timed t(c, D3_K_QKV, s);
                 D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
             }
-            RopeArgs r{};
-            r.qkv = qkv; r.k_cache = k_layer; r.v_cache = v_layer; r.rope_cs = rope_cs;
-            r.cm = cm; r.ncols = ncols; r.H = d.n_heads; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
-            D3_HIP(launch_rope_append(r, d.kv_dtype, s));
+            if (!rope_in_attn) {
+                RopeArgs r{};
+                r.qkv = qkv; r.k_cache = k_layer; r.v_cache = v_layer; r.rope_cs = rope_cs;
+                r.cm = cm; r.ncols = ncols; r.H = d.n_heads; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
+                D3_HIP(launch_rope_append(r, d.kv_dtype, s));
+            }
         } else {
             // the GEMV epilogue rotates q and k and appends the new K/V row itself
             g.x = x; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
@@ -373,6 +379,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         at.split_len = split_len; at.n_splits = n_splits;
         at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml); at.tickets = c->at<int>(c->lay.tickets);
         at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
+        at.rope_cs = rope_in_attn ? rope_cs : nullptr;
         {
             Timed t(c, D3_K_ATTN, s);
             D3_HIP(launch_attention(at, d.kv_dtype, s));

@@ -129,7 +129,8 @@ struct RopeArgs {
 int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s);
 
 struct AttnArgs {
-    const float* q;        // [ncols][q_stride], rotated
+    const float* q;        // [ncols][q_stride]: q heads, then (rope_cs set) the newest k and v rows; rotated unless rope_cs is set
+    const float2* rope_cs; // optional [ncols][hd/2] (cos, sin): rotate q and k here and append the newest K/V row
     int q_stride;
     const void* k_cache;   // this block's cache
     const void* v_cache;

@@ -123,8 +123,8 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
             const int j = j0 + ((it0 + u) * NW + wave) * RPW + rg;
             const int jc = j < j1 ? j : j1 - 1;
             if (it0 + u < iters) {
-                kv[u] = *reinterpret_cast<const uint4*>(Kb + (size_t)jc * HD + sub * EPL);
-                vv[u] = *reinterpret_cast<const uint4*>(Vb + (size_t)jc * HD + sub * EPL);
+                kv[u] = __builtin_bit_cast(uint4, load_stream16(Kb + (size_t)jc * HD + sub * EPL));   // each row is read once per step
+                vv[u] = __builtin_bit_cast(uint4, load_stream16(Vb + (size_t)jc * HD + sub * EPL));
             }
         }
     };
@@ -289,11 +289,23 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
             L += sh.l[g][w] * f;
             o += sh.o[g][w][t] * f;
         }
+        if (n_live == 1) {                             // the only split of this column: the result is final
+            const float r = o / L;
+            const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
+            if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
+            if (a.out_hi) {
+                const uint32_t hb = f32_to_bf16(r);
+                a.out_hi[oi] = (bf16_t)hb;
+                a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+            }
+            continue;
+        }
         const size_t pidx = ((size_t)c * a.H + h0 + g) * a.n_splits + split;
         st_agent(&a.part_o[pidx * HD + t], o);
         if (t == 0) { st_agent(&a.part_ml[pidx * 2], M); st_agent(&a.part_ml[pidx * 2 + 1], L); }
     }
 
+    if (n_live == 1) return;
     // ---- the split that arrives last merges all splits of this (column, KV head) ----
     wait_stores();                                     // this split's partials have reached the coherence point
     __syncthreads();

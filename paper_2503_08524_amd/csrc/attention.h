@@ -317,37 +317,51 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     }
     __syncthreads();
     if (!sh.is_last) return;
-    for (int idx = tid; idx < G * HD; idx += NW * 64) {
-        const int g = idx / HD, t = idx % HD;
-        // all partials are fetched in rounds of 8 splits (one round trip each), merged with a running max
-        const size_t p0 = ((size_t)c * a.H + h0 + g) * a.n_splits;
-        float gm = -INFINITY, L = 0.f, o = 0.f;
-        for (int s0 = 0; s0 < n_live; s0 += 8) {
-            float ms[8], ls[8], os[8];
+    // every thread owns ITEMS (head, element) outputs; the partials of all of them are fetched together, in rounds
+    // of 8 splits (one round trip per round), and merged with a running max
+    constexpr int ITEMS = (G * HD + NW * 64 - 1) / (NW * 64);
+    float gm[ITEMS], L[ITEMS], o[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) { gm[i] = -INFINITY; L[i] = 0.f; o[i] = 0.f; }
+    for (int s0 = 0; s0 < n_live; s0 += 8) {
+        float ms[ITEMS][8], ls[ITEMS][8], os[ITEMS][8];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            int idx = tid + i * (NW * 64);
+            idx = idx < G * HD ? idx : G * HD - 1;
+            const size_t p0 = ((size_t)c * a.H + h0 + idx / HD) * a.n_splits;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
-                ms[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
-                ls[k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
-                os[k] = ld_agent(&a.part_o[(p0 + sidx) * HD + t]);
+                ms[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
+                ls[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
+                os[i][k] = ld_agent(&a.part_o[(p0 + sidx) * HD + idx % HD]);
             }
-            float rm = gm;
+        }
 #pragma unroll
-            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[k]);
-            const float keep = exp2f(gm - rm);            // gm = -inf on the first round: exp2(-inf) = 0
-            L *= keep; o *= keep;
+        for (int i = 0; i < ITEMS; ++i) {
+            float rm = gm[i];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[i][k]);
+            const float keep = exp2f(gm[i] - rm);         // -inf on the first round: exp2(-inf) = 0
+            L[i] *= keep; o[i] *= keep;
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 if (s0 + k < n_live) {
-                    const float w = exp2f(ms[k] - rm);
-                    L += ls[k] * w;
-                    o += os[k] * w;
+                    const float w = exp2f(ms[i][k] - rm);
+                    L[i] += ls[i][k] * w;
+                    o[i] += os[i][k] * w;
                 }
             }
-            gm = rm;
+            gm[i] = rm;
         }
-        const float r = o / L;
-        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int idx = tid + i * (NW * 64);
+        if (idx >= G * HD) continue;
+        const float r = o[i] / L[i];
+        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + idx / HD) * HD + idx % HD;
         if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
         if (a.out_hi) {
             const uint32_t hb = f32_to_bf16(r);

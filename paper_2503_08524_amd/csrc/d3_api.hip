@@ -99,7 +99,7 @@ struct d3_ctx {
     Layout lay;
     int n_cu;
     int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
-    int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 2)
+    int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
     bool has_plan;
@@ -171,7 +171,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->k_cache = static_cast<char*>(k_cache); c->v_cache = static_cast<char*>(v_cache); c->ws = static_cast<char*>(workspace);
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
-    c->gemv_wgs_per_cu = 2;
+    c->gemv_wgs_per_cu = 3;
     c->gemv_head_start = 0;
     if (const char* env = getenv("D3_GEMV_HEAD_START")) { const int v = atoi(env); if (v >= 0 && v <= 64) c->gemv_head_start = v; }
     if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {

@@ -310,6 +310,9 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* 
         if (waves < 4) continue;
         if (waves_forced) waves = waves_forced;
         best_rt = rt; best_waves = waves;
+        // a gate/up pair doubles the bytes a wave keeps in flight: with workgroups to spare (>= 3 per CU at RT = 2)
+        // one tile pair per wave ran faster (70B shape: 160 vs 176 us)
+        if (!rt_forced && mode == MODE_SWIGLU && rt == 2 && tiles / 2 >= 3 * n_cu) continue;
         if (rt_forced ? rt <= rt_forced : (10 * (tiles / rt) >= 6 * n_cu && (long long)(tiles / rt) * waves >= 4LL * n_cu)) break;
     }
     if (n_groups) *n_groups = tiles / best_rt;

@@ -27,7 +27,10 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_alu_kernel(GemvArgs a) {
     __shared__ GemvEpBuf<NC> ep[kGemvWaves];
     constexpr int R = kGemvStageR / NC;
     const int tid = threadIdx.x, wave = tid >> 6;
-    const int gw = blockIdx.x * kGemvWaves + wave, nw = gridDim.x * kGemvWaves;
+    // Units go round-robin over the waves of the whole grid, so that at any moment the chip streams one contiguous
+    // band of the matrix (spread over every memory channel); numbering the waves workgroup-fastest hands the units
+    // that do not divide evenly to different workgroups, one each.
+    const int gw = wave * gridDim.x + blockIdx.x, nw = gridDim.x * kGemvWaves;
     if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 0] = wall_clock64();
     GemvStageRegs<NC, R> regs;
     GemvPipe<W, kGemvDepth> pipe;
@@ -47,20 +50,10 @@ template <typename W, int NC>
 int launch_nc(const GemvArgs& a, int mode, bool norm, int n_wg, hipStream_t s) {
     const size_t lds = (size_t)NC * gemv_f4_per_col<W>(a.K) * sizeof(float4);
     const int n_units = gemv_n_units(a, mode);
-    // n_wg workgroups is the nominal size; up to 1.5x as many are allowed when that splits the units evenly over
-    // the waves (every wave then runs the same number of units: 11008 gate/up units are 4 each on 2752 waves,
-    // but 5 or 6 each on 2048).  The last round of a kernel costs as much as any other.
+    // n_wg workgroups, a multiple of the CU count (a compute unit is the unit of bandwidth: the same number of
+    // workgroups on each makes them finish together); fewer when there are not four units for each
     int grid = (n_units + kGemvWaves - 1) / kGemvWaves;
-    if (grid > n_wg) {
-        double best = 2.0;
-        for (int g = n_wg; g <= n_wg + n_wg / 2; ++g) {
-            const long long waves = (long long)g * kGemvWaves;
-            const long long rounds = (n_units + waves - 1) / waves;
-            const double idle = (double)(rounds * waves - n_units) / (double)(rounds * waves);   // idle share of the wave-rounds
-            if (idle < best - 1e-9) { best = idle; grid = g; }
-            if (idle == 0.0) break;
-        }
-    }
+    if (grid > n_wg) grid = n_wg;
     if ((long long)grid * kGemvWaves * kGemvEpCap < n_units) return (int)hipErrorInvalidValue;   // a wave parks at most kGemvEpCap (= 64 lanes) units
 #define D3_LAUNCH(MODE, NORM) hipLaunchKernelGGL((gemv_alu_kernel<W, NC, MODE, NORM>), dim3(grid), dim3(kGemvThreads), lds, s, a)
     if (mode == MODE_STORE) { if (norm) D3_LAUNCH(MODE_STORE, true); else D3_LAUNCH(MODE_STORE, false); }

@@ -183,9 +183,9 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "decode_7b_b1_hbm_traffic.json")
     if args.config == "7b" and kclass == binding.D3_K_GATE_UP and os.path.exists(tpath):
         with open(tpath) as f:
-            k = json.load(f)["kernels"].get("gemv_alu_kernel<unsigned short, 1, 2, true>")
-        if k:
-            traffic = k["fetch_bytes_per_launch"] + k["write_bytes_per_launch"]
+            ks = [v for name, v in json.load(f)["kernels"].items() if "gemv_alu_kernel<unsigned short, 1, 2, true>" in name]
+        if ks:
+            traffic = ks[0]["fetch_bytes_per_launch"] + ks[0]["write_bytes_per_launch"]
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                 "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": bytes_per_launch}

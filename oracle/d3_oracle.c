@@ -277,6 +277,31 @@ int d3o_forward_token(d3o_seq *s, int32_t token, int32_t pos, const int32_t *lay
     return 0;
 }
 
+/* The steps of d3o_forward_token up to the cache write of the first listed block, and nothing after them:
+ * embedding -> RMSNorm -> Wk, Wv -> RoPE(k) -> K[layer][pos], V[layer][pos].  A test that needs a long prompt's
+ * cache rows of the first block, but not the prompt's outputs, fills the cache this way. */
+int d3o_first_block_kv(d3o_seq *s, int32_t token, int32_t pos, int32_t layer)
+{
+    if (!s || pos < 0 || pos >= s->max_seq) return -1;
+    const d3o_model *m = s->m;
+    const d3o_config *c = &m->cfg;
+    if (token < 0 || token >= c->V || layer < 0 || layer >= c->L) return -1;
+    const int32_t d = c->d, hd = c->hd, kv_dim = c->H_kv * hd;
+    const int32_t dt = c->weight_dtype;
+    const d3o_layer *w = &m->layers[layer];
+    real *x = (real *)malloc(sizeof(real) * d);
+    real *a = (real *)malloc(sizeof(real) * d);
+    real *k_row = s->K + kv_index(s, layer, pos);
+    real *v_row = s->V + kv_index(s, layer, pos);
+    for (int32_t j = 0; j < d; ++j) x[j] = weight_at(m->tok_emb, dt, (size_t)token * d + j);
+    rmsnorm(x, w->attn_norm, d, (real)c->eps, a);
+    matvec(w->wk, dt, kv_dim, d, a, k_row);
+    matvec(w->wv, dt, kv_dim, d, a, v_row);
+    for (int32_t h = 0; h < c->H_kv; ++h) rope(k_row + (size_t)h * hd, hd, pos, c->rope_base);
+    free(x); free(a);
+    return 0;
+}
+
 int32_t d3o_argmax(const double *logits, int32_t n)
 {
     int32_t best = 0;

@@ -75,6 +75,10 @@ void d3o_seq_free(d3o_seq *);
 int d3o_forward_token(d3o_seq *, int32_t token, int32_t pos, const int32_t *layer_ids, int32_t n_ids,
                       double *hidden_out, double *logits_out);
 
+/* Only the cache write of d3o_forward_token(token, pos, {layer}): K[layer][pos], V[layer][pos] of a token that
+ * enters `layer` as its bare embedding (same steps, same order; the rest of the block is not run). */
+int d3o_first_block_kv(d3o_seq *, int32_t token, int32_t pos, int32_t layer);
+
 /* Lowest index of the maximum. */
 int32_t d3o_argmax(const double *logits, int32_t n);
 

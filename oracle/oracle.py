@@ -48,6 +48,8 @@ def _lib(variant: str) -> C.CDLL:
         lib.d3o_seq_free.argtypes = [vp]
         lib.d3o_forward_token.argtypes = [vp, i32, i32, vp, i32, vp, vp]
         lib.d3o_forward_token.restype = C.c_int
+        lib.d3o_first_block_kv.argtypes = [vp, i32, i32, i32]
+        lib.d3o_first_block_kv.restype = C.c_int
         lib.d3o_argmax.argtypes = [vp, i32]
         lib.d3o_argmax.restype = i32
         lib.d3o_fill_missing_kv.argtypes = [vp, i32, i32, i32]
@@ -143,6 +145,11 @@ class OracleSeq:
         if rc != 0:
             raise ValueError("d3o_forward_token: invalid arguments")
         return hidden, logits
+
+    def first_block_kv(self, token: int, pos: int, layer: int) -> None:
+        """Only the cache write of forward_token(token, pos, [layer])."""
+        if self.model.lib.d3o_first_block_kv(self.handle, int(token), int(pos), int(layer)) != 0:
+            raise ValueError("d3o_first_block_kv: invalid arguments")
 
     def fill_missing_kv(self, pos: int, drop_begin: int, n_drop: int) -> None:
         if self.model.lib.d3o_fill_missing_kv(self.handle, pos, drop_begin, n_drop) != 0:

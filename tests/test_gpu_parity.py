@@ -175,3 +175,72 @@ def test_full_size_7b_configuration_sampled_against_oracle():
         src = s - 1
         assert torch.equal(dec.k_cache[s, 0, :, pos], dec.k_cache[src, 0, :, pos])
         assert torch.equal(dec.v_cache[s + n - 1, 0, :, pos], dec.v_cache[src, 0, :, pos])
+
+
+@pytest.mark.timeout(400)
+@pytest.mark.parametrize("name,B,P", [("llama-13b", 4, 1024), ("llama-7b", 32, 2048), ("llama-70b", 8, 1024)])
+def test_full_size_batched_configurations_sampled_against_oracle(name, B, P):
+    """The batched benchmark configurations in their own launch configuration (all blocks, full batch, full prompt),
+    checked on what the oracle can afford for two sampled sequences (the first and the last of the batch): the hidden
+    state after block 0 of the last prompt position and of every decode step, and the complete logits of the steps that
+    keep only block 0 / no block (alpha = 0.5 halves the depth every step).  All blocks point at the same weight
+    tensors, so the host draws one block.  For a sampled sequence the oracle fills block 0's cache rows of the prompt
+    with its cache-write-only entry (those rows depend on the embeddings alone) and runs block 0 in full for the rows
+    that are compared."""
+    import torch
+    from oracle import oracle
+    from paper_2503_08524_amd import binding
+
+    full = d3_inputs.SHAPES[name]
+    one = full.truncated(1)
+    w1 = d3_inputs.make_weights(one, 0)
+    alpha, start = 0.5, d3_inputs.start_layer_from_fraction(full.L, 0.6)
+    G = int(np.floor(np.log2(full.L))) + 2                       # depth L, L/2, ..., 1, 0
+    keep, drop, ids = binding.d3_plan_depth(full.L, alpha, start, 0, G)
+    assert keep[0] == full.L and keep[G - 2] == 1 and keep[G - 1] == 0 and all(ids[i, 0] == 0 for i in range(G - 1))
+    prompts = d3_inputs.make_prompt(B, P, full.V, seed=1)
+    forced = _forced(B, G, full.V, 17)
+
+    dev = binding.weights_to_device(one, w1)
+    dev_tied = dict(dev)
+    dev_tied["layers"] = [dev["layers"][0]] * full.L
+    dec = binding.Decoder(full, dev_tied, B, P + G)
+    print(f"case full-size {name} B={B} P={P}, tied blocks", flush=True)
+    gpu = helpers.gpu_generate(full, None, prompts, G, alpha, start, forced=forced, decoder=dec, fill_each_step=True)
+
+    oracle.set_threads(helpers.oracle_threads())
+    model = oracle.OracleModel(one, w1)
+    def rel(a, b):
+        return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+    worst_l = worst_h = 0.0
+    for b in (0, B - 1):
+        seq = model.new_seq(P + G)
+        for p in range(P - 1):
+            seq.first_block_kv(int(prompts[b, p]), p, 0)
+        hid, _ = seq.forward_token(int(prompts[b, P - 1]), P - 1, [0], want_hidden=True)
+        e = rel(gpu["hidden"][0][1, b].astype(np.float64), hid[1])
+        worst_h = max(worst_h, e)
+        assert e <= helpers.HIDDEN_REL_L2, f"seq {b} prompt: hidden rel L2 {e:.3e}"
+        for i in range(1, G):
+            blocks = [0] if keep[i] >= 1 else []
+            h, lg = seq.forward_token(int(forced[b, i - 1]), P + i - 1, blocks, want_hidden=True, want_logits=True)
+            got = gpu["hidden"][i][:, b].astype(np.float64)
+            assert rel(got[0], h[0]) <= 1e-6                               # the embedding row
+            if keep[i] >= 1:
+                e = rel(got[1], h[1])
+                worst_h = max(worst_h, e)
+                assert e <= helpers.HIDDEN_REL_L2, f"seq {b} step {i}: hidden rel L2 {e:.3e}"
+            if keep[i] <= 1:                                                # logits depend on block 0 at most
+                err = float(np.abs(gpu["logits"][i][b].astype(np.float64) - lg).max())
+                worst_l = max(worst_l, err)
+                assert err <= helpers.LOGIT_ATOL, f"seq {b} step {i}: logits max abs err {err:.3e}"
+                top2 = np.partition(lg, -2)[-2:]
+                if top2[1] - top2[0] > helpers.TOKEN_MARGIN:
+                    assert int(gpu["tokens"][i][b]) == oracle.argmax(lg)
+    print(f"  worst logit abs err {worst_l:.3e}, worst hidden rel L2 {worst_h:.3e}", flush=True)
+    # the fill of the dropped blocks copied the source block's rows (bit-exact), at full cache size
+    i = 1
+    pos, s, n = P + i - 1, int(drop[i]), full.L - int(keep[i])
+    assert s >= 1 and torch.equal(dec.k_cache[s, B - 1, :, pos], dec.k_cache[s - 1, B - 1, :, pos])
+    assert torch.equal(dec.v_cache[s + n - 1, 0, :, pos], dec.v_cache[s - 1, 0, :, pos])
+    dec.close()

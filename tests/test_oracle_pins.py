@@ -243,3 +243,22 @@ def test_threads_do_not_change_results():
     b = oracle.generate(model, prompt, 4, 0.9, 3)
     oracle.set_threads(1)
     assert all((x == y).all() for x, y in zip(a.logits, b.logits))
+
+
+def test_first_block_cache_write_alone_equals_the_full_forward():
+    """d3o_first_block_kv writes exactly the K/V row that forward_token writes for the first listed block (bitwise),
+    and nothing else; the brute force agrees with both."""
+    shape = d3_inputs.TINY
+    w = d3_inputs.make_weights(shape, 3)
+    model = oracle.OracleModel(shape, w)
+    toks = d3_inputs.make_prompt(1, 5, shape.V, seed=9)[0]
+    full, only = model.new_seq(8), model.new_seq(8)
+    for layer in (0, 2):
+        for p, t in enumerate(toks):
+            full.forward_token(int(t), p, [layer, 3] if layer < 3 else [layer])
+            only.first_block_kv(int(t), p, layer)
+            kf, vf = full.get_kv(layer, p)
+            ko, vo = only.get_kv(layer, p)
+            assert np.array_equal(kf, ko) and np.array_equal(vf, vo)
+            k3, v3 = only.get_kv(3, p)
+            assert not k3.any() and not v3.any()          # no other block's row was touched

@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 import d3_inputs  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+FILL_MODES = {}
 
 CONFIGS = {
     # name: (shape, B, P, G, alphas (first is the headline), start fraction)
@@ -45,20 +46,23 @@ def block_weight_bytes(s) -> int:
     return s.params_per_block * (4 if s.dtype == "f32" else 2)
 
 
-def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem):
+def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy"):
     """HBM bytes the method must move over decode steps 1..G-1: weights of the executed blocks,
-    their KV rows read and appended, the fill of the dropped blocks, lm_head."""
+    their KV rows read and appended, the fill of the dropped blocks (COPY: read one row, write it;
+    RECOMPUTE: stream W_k and W_v of every dropped block, write its row), lm_head."""
     wb = block_weight_bytes(s)
     kv_row = 2 * s.H_kv * s.hd * kv_bytes_per_elem          # K + V of one token in one block
     head = s.V * s.d * (4 if s.dtype == "f32" else 2)
     total = 0
     for i in range(1, G):
         k, n = int(keep[i]), s.L - int(keep[i])
-        total += k * (wb + kv_row * B * (P + i) + kv_row * B) + n * 2 * kv_row * B + head
+        per_dropped = {"copy": 2 * kv_row * B, "none": 0,
+                       "recompute": 2 * s.H_kv * s.hd * s.d * (4 if s.dtype == "f32" else 2) + kv_row * B}[fill]
+        total += k * (wb + kv_row * B * (P + i) + kv_row * B) + n * per_dropped + head
     return total
 
 
-def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill=True):
+def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy"):
     """`requests` whole generation phases back to back; returns seconds (host clock around a device sync)."""
     cur = first_tok.clone()
     nxt = torch.zeros_like(cur)
@@ -70,8 +74,8 @@ def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill=True):
         cur.copy_(first_tok)
         for i in range(1, G):
             dec.decode_step(cur, i, nxt)
-            if fill:
-                dec.fill_missing_kv(P + i - 1, P + i)
+            if fill != "none":
+                dec.fill_missing_kv(P + i - 1, P + i, FILL_MODES[fill])
             cur, nxt = nxt, cur
     dec.sync_check()
     return time.perf_counter() - t0
@@ -109,7 +113,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="7b", choices=sorted(CONFIGS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-fill", action="store_true")
+    ap.add_argument("--no-fill", action="store_true", help="same as --fill none")
+    ap.add_argument("--fill", default="copy", choices=["copy", "recompute", "none"],
+                    help="missing-state fill after every decode step (Section 3.2): KV copy (default), KV recompute, or none")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -117,6 +123,8 @@ def main() -> int:
 
     import torch
     from paper_2503_08524_amd import binding
+    FILL_MODES.update(copy=binding.D3_FILL_COPY, recompute=binding.D3_FILL_RECOMPUTE)
+    fill = "none" if args.no_fill else args.fill
 
     shape, B, P, G, alphas, start_frac = CONFIGS[args.config]
     start = d3_inputs.start_layer_from_fraction(shape.L, start_frac)
@@ -136,6 +144,8 @@ def main() -> int:
     del cal_src, cal_dst
 
     dec.set_plan(alphas[0], start, 0, G)
+    if fill == "recompute":
+        dec.set_fill_mode(binding.D3_FILL_RECOMPUTE)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     first_tok = dec.prefill(prompts)
@@ -146,10 +156,10 @@ def main() -> int:
     results = {}
     for alpha in alphas:
         keep, _, _ = binding.d3_plan_depth(shape.L, alpha, start, 0, G)
-        run_decode(dec, torch, first_tok, P, G, alpha, start, args.warmup, not args.no_fill)
-        secs = run_decode(dec, torch, first_tok, P, G, alpha, start, args.steps, not args.no_fill)
+        run_decode(dec, torch, first_tok, P, G, alpha, start, args.warmup, fill)
+        secs = run_decode(dec, torch, first_tok, P, G, alpha, start, args.steps, fill)
         n_tok = args.steps * (G - 1) * B
-        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes) * args.steps
+        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes, fill) * args.steps
         results[alpha] = {
             "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (args.steps * (G - 1)) * 1e3,
             "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (args.steps * (G - 1)) / 1e9,
@@ -173,7 +183,7 @@ def main() -> int:
         kernel = "fused RMSNorm + gate/up + SiLU*mul projection"
         kclass, bytes_per_launch = binding.D3_K_GATE_UP, 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4
     dec.profile_select(kclass)
-    run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, False)
+    run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, "none")
     ms, n = dec.profile_read()
     dec.profile_select(binding.D3_K_NONE)
     achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9 if n else 0.0
@@ -200,7 +210,7 @@ def main() -> int:
         "config": {"workload": f"{shape.name} B={B} P={P} G={G} alpha={alphas[0]} start_layer={start}",
                    "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
                    "persistent_step_workgroups": dec.persistent_workgroups,
-                   "fill_every_step": not args.no_fill},
+                   "fill_every_step": fill},
         "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
         "by_alpha": {str(a): r for a, r in results.items()},
         "roofline": roofline,

@@ -39,7 +39,7 @@ typedef enum {
 } d3_status;
 
 typedef enum { D3_F32 = 0, D3_BF16 = 1, D3_F16 = 2 } d3_dtype;
-typedef enum { D3_FILL_COPY = 0 } d3_fill_mode;
+typedef enum { D3_FILL_COPY = 0, D3_FILL_RECOMPUTE = 1 } d3_fill_mode;
 
 typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
@@ -128,10 +128,23 @@ int d3_decode_step(d3_ctx *ctx, const int32_t *tok_in, int32_t step_i, int32_t *
  * and every block l that step dropped, K[l][.][p], V[l][.][p] <- K[src][.][p],
  * V[src][.][p], where src is the last executed block before the drop window
  * (the first one after it when the window starts at block 0; zeros when no
- * block ran).  mode must be D3_FILL_COPY.  Rows written by the prompt pass need
- * nothing.  May be called every step with a one-row range or once before the
- * cache is reused; the result is the same. */
+ * block ran).  Rows written by the prompt pass need nothing.  D3_FILL_COPY may be
+ * called every step with a one-row range or once before the cache is reused;
+ * the result is the same.
+ * D3_FILL_RECOMPUTE (Section 3.2: hidden state copied, KV recomputed, as in
+ * CALM): K[l][.][p] = RoPE(W_k^l a), V[l][.][p] = W_v^l a with a = RMSNorm_l(h),
+ * h = the residual that entered the drop window of the step that wrote row p
+ * (the embedding when the window starts at block 0).  Needs
+ * d3_set_fill_mode(ctx, D3_FILL_RECOMPUTE) before that decode step, and fills
+ * the row of the latest decode step only: [pos_begin, pos_end) must be
+ * [n_ctx - 1, n_ctx), else D3_ESTATE.  Streams W_k, W_v of every dropped block. */
 int d3_fill_missing_kv(d3_ctx *ctx, int32_t pos_begin, int32_t pos_end, int32_t mode, void *hip_stream);
+
+/* Which fill the caller will use.  With D3_FILL_RECOMPUTE every decode step keeps the
+ * residual that enters its drop window (one device copy of [B][d_model] floats per
+ * step) for the d3_fill_missing_kv call that follows it.  Default D3_FILL_COPY.
+ * D3_ESTATE with the persistent decode step. */
+int d3_set_fill_mode(d3_ctx *ctx, int32_t mode);
 
 /* Current number of cache rows per sequence. */
 int32_t d3_n_ctx(const d3_ctx *ctx);

@@ -12,7 +12,10 @@ code asserts it).
 
 With fill=True, a row that skipped block l instead exposes, in block l, the K/V
 it produced in the last block before its drop window (the COPY policy of
-Section 3.2); this is only supported for start >= 1.
+Section 3.2); this is only supported for start >= 1.  With fill="recompute" it
+exposes instead the K/V that block l's own projections make of the row's current
+residual, i.e. of the hidden state copied through the skipped blocks (the
+recompute policy of the same passage).
 """
 from __future__ import annotations
 
@@ -67,7 +70,7 @@ def forward_all(shape, w64, tokens: Sequence[int], row_blocks: List[Sequence[int
     for l in range(s.L):
         act = np.nonzero(runs[:, l])[0]
         if act.size == 0:
-            continue
+            continue                           # (nobody reads this block's rows either)
         lw = w64["layers"][l]
         A = _rms(X[act], lw["attn_norm"], s.eps)
         Q = _rope_all((A @ lw["wq"].T).reshape(-1, s.H, s.hd), pos[act], s.hd, s.rope_base)
@@ -76,7 +79,14 @@ def forward_all(shape, w64, tokens: Sequence[int], row_blocks: List[Sequence[int
         Kf = np.zeros((S, s.H_kv, s.hd)); Vf = np.zeros((S, s.H_kv, s.hd))
         have = np.zeros(S, bool)
         Kf[act], Vf[act], have[act] = K, V, True
-        if fill:                               # skipped rows expose their source block's K/V here
+        if fill == "recompute":                # skipped rows expose the K/V this block makes of their copied hidden state
+            idle = np.nonzero(~runs[:, l])[0]
+            if idle.size:
+                Ai = _rms(X[idle], lw["attn_norm"], s.eps)
+                Kf[idle] = _rope_all((Ai @ lw["wk"].T).reshape(-1, s.H_kv, s.hd), pos[idle], s.hd, s.rope_base)
+                Vf[idle] = (Ai @ lw["wv"].T).reshape(-1, s.H_kv, s.hd)
+                have[idle] = True
+        elif fill:                             # skipped rows expose their source block's K/V here
             for t in np.nonzero(~runs[:, l])[0]:
                 src = row_src[t]
                 assert src is not None and src < l and runs[t, src]

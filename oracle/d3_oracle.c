@@ -330,6 +330,32 @@ int d3o_fill_missing_kv(d3o_seq *s, int32_t pos, int32_t drop_begin, int32_t n_d
     return 0;
 }
 
+/* RECOMPUTE fill (Section 3.2: the hidden state is copied through the skipped blocks and their KV is
+ * recomputed from it): for every block l in [drop_begin, drop_begin + n_drop),
+ * a = RMSNorm(h; attn_norm_l), K[l][pos] = RoPE(W_k^l a, pos), V[l][pos] = W_v^l a. */
+int d3o_fill_recompute(d3o_seq *s, int32_t pos, int32_t drop_begin, int32_t n_drop, const double *h)
+{
+    if (!s || !h || pos < 0 || pos >= s->max_seq) return -1;
+    const d3o_model *m = s->m;
+    const d3o_config *c = &m->cfg;
+    if (n_drop < 0 || drop_begin < 0 || drop_begin + n_drop > c->L) return -1;
+    const int32_t d = c->d, hd = c->hd, kv_dim = c->H_kv * hd;
+    real *x = (real *)malloc(sizeof(real) * d);
+    real *a = (real *)malloc(sizeof(real) * d);
+    for (int32_t j = 0; j < d; ++j) x[j] = (real)h[j];
+    for (int32_t l = drop_begin; l < drop_begin + n_drop; ++l) {
+        const d3o_layer *w = &m->layers[l];
+        real *k_row = s->K + kv_index(s, l, pos);
+        real *v_row = s->V + kv_index(s, l, pos);
+        rmsnorm(x, w->attn_norm, d, (real)c->eps, a);
+        matvec(w->wk, c->weight_dtype, kv_dim, d, a, k_row);
+        matvec(w->wv, c->weight_dtype, kv_dim, d, a, v_row);
+        for (int32_t hh = 0; hh < c->H_kv; ++hh) rope(k_row + (size_t)hh * hd, hd, pos, c->rope_base);
+    }
+    free(x); free(a);
+    return 0;
+}
+
 int d3o_get_kv(const d3o_seq *s, int32_t layer, int32_t pos, double *k_out, double *v_out)
 {
     if (!s || layer < 0 || layer >= s->m->cfg.L || pos < 0 || pos >= s->max_seq) return -1;

@@ -87,6 +87,11 @@ int32_t d3o_argmax(const double *logits, int32_t n);
  * src = drop_begin - 1, or drop_begin + n_drop if drop_begin == 0; zeros if no block ran. */
 int d3o_fill_missing_kv(d3o_seq *, int32_t pos, int32_t drop_begin, int32_t n_drop);
 
+/* RECOMPUTE fill (Section 3.2, CALM-style): h [d] is the hidden state copied through the skipped blocks
+ * (the residual that entered the drop window); for every block l in [drop_begin, drop_begin + n_drop):
+ * K[l][pos] = RoPE(W_k^l RMSNorm_l(h)), V[l][pos] = W_v^l RMSNorm_l(h). */
+int d3o_fill_recompute(d3o_seq *, int32_t pos, int32_t drop_begin, int32_t n_drop, const double *h);
+
 /* Read one cache row (K and V, each [H_kv*hd]) as doubles. */
 int d3o_get_kv(const d3o_seq *, int32_t layer, int32_t pos, double *k_out, double *v_out);
 

@@ -54,6 +54,8 @@ def _lib(variant: str) -> C.CDLL:
         lib.d3o_argmax.restype = i32
         lib.d3o_fill_missing_kv.argtypes = [vp, i32, i32, i32]
         lib.d3o_fill_missing_kv.restype = C.c_int
+        lib.d3o_fill_recompute.argtypes = [vp, i32, i32, i32, vp]
+        lib.d3o_fill_recompute.restype = C.c_int
         lib.d3o_get_kv.argtypes = [vp, i32, i32, vp, vp]
         lib.d3o_get_kv.restype = C.c_int
         lib.d3o_rmsnorm.argtypes = [vp, vp, i32, dbl, vp]
@@ -155,6 +157,12 @@ class OracleSeq:
         if self.model.lib.d3o_fill_missing_kv(self.handle, pos, drop_begin, n_drop) != 0:
             raise ValueError("d3o_fill_missing_kv: invalid arguments")
 
+    def fill_recompute(self, pos: int, drop_begin: int, n_drop: int, h: np.ndarray) -> None:
+        """RECOMPUTE fill of row pos from the hidden state h that entered the drop window."""
+        h = np.ascontiguousarray(h, np.float64)
+        if self.model.lib.d3o_fill_recompute(self.handle, pos, drop_begin, n_drop, _ptr(h)) != 0:
+            raise ValueError("d3o_fill_recompute: invalid arguments")
+
     def get_kv(self, layer: int, pos: int):
         s = self.model.shape
         k = np.zeros(s.H_kv * s.hd, np.float64)
@@ -217,11 +225,18 @@ def generate(model: OracleModel, prompt: Sequence[int], G: int, alpha: float, st
     return out
 
 
-def fill_generated_rows(gen: Generation, P: int, G: int, pos_begin: int = 0) -> None:
-    """COPY fill of every row written by decode steps 1..G-1 of `gen`."""
+def fill_generated_rows(gen: Generation, P: int, G: int, pos_begin: int = 0, mode: str = "copy") -> None:
+    """COPY (or RECOMPUTE) fill of every row written by decode steps 1..G-1 of `gen`.  RECOMPUTE needs the hidden
+    states that generate() recorded: the state copied through a step's drop window is the one after the executed
+    blocks that precede the window (the embedding when there are none)."""
     L = gen.seq.model.shape.L
     for i in range(1, G):
-        gen.seq.fill_missing_kv(pos_begin + P + i - 1, int(gen.drop_begin[i]), int(L - gen.keep[i]))
+        s, n = int(gen.drop_begin[i]), int(L - gen.keep[i])
+        if mode == "copy":
+            gen.seq.fill_missing_kv(pos_begin + P + i - 1, s, n)
+        else:
+            before = int((gen.layer_ids[i, : gen.keep[i]] < s).sum())
+            gen.seq.fill_recompute(pos_begin + P + i - 1, s, n, gen.hidden[i][before])
 
 
 # ---- sub-functions (for the pins) ----

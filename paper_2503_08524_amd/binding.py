@@ -15,6 +15,7 @@ _LIB: Optional[C.CDLL] = None
 
 D3_F32, D3_BF16, D3_F16 = 0, 1, 2
 D3_FILL_COPY = 0
+D3_FILL_RECOMPUTE = 1
 D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD, D3_K_STEP = range(8)
 
 
@@ -60,6 +61,7 @@ def load_library() -> C.CDLL:
         lib.d3_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
         lib.d3_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
         lib.d3_fill_missing_kv.argtypes = [vp, i32, i32, i32, vp]
+        lib.d3_set_fill_mode.argtypes = [vp, i32]
         lib.d3_n_ctx.argtypes = [vp]
         lib.d3_n_ctx.restype = i32
         lib.d3_truncate.argtypes = [vp, i32]
@@ -171,6 +173,9 @@ class Decoder:
 
     def fill_missing_kv(self, pos_begin: int, pos_end: int, mode: int = D3_FILL_COPY) -> None:
         _check(self.lib.d3_fill_missing_kv(self.ctx, pos_begin, pos_end, mode, self._stream()))
+
+    def set_fill_mode(self, mode: int) -> None:
+        _check(self.lib.d3_set_fill_mode(self.ctx, mode))
 
     def sync_check(self) -> None:
         """Synchronise the stream; raises if a persistent decode step gave up at a grid barrier."""

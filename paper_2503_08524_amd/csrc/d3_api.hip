@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -83,6 +83,7 @@ Layout make_layout(const d3_model_desc& d) {
     l.n_hi = take(C * d.d_model * 2);
     l.n_lo = take(C * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
+    l.h_skip = take(C * d.d_model * 4);
     l.cand_val = take(4096 * 4);
     l.cand_idx = take(4096 * 4);
     l.total = o;
@@ -109,6 +110,8 @@ struct d3_ctx {
     bool prefilled;
     int B, n_ctx, last_step;
     std::vector<int32_t> row_drop_begin, row_n_drop;   // per cache row: what the step that wrote it dropped
+    int fill_mode;                // D3_FILL_RECOMPUTE: decode steps keep the residual that enters their drop window
+    int skip_row;                 // cache row whose residual h_skip holds (-1: none)
 
     // persistent one-launch decode step (batch 1, bf16 weights, head_dim 128)
     bool mega_ok;
@@ -183,6 +186,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->prof_class = D3_K_NONE; c->prof_used = 0;
     c->has_plan = false; c->n_steps = 0;
     c->prefilled = false; c->B = 0; c->n_ctx = 0; c->last_step = 0;
+    c->fill_mode = D3_FILL_COPY;
+    c->skip_row = -1;
     c->row_drop_begin.assign(desc->max_seq, 0);
     c->row_n_drop.assign(desc->max_seq, 0);
 
@@ -284,10 +289,29 @@ void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split
     *n_splits = n;
 }
 
+// ALU path: a projection takes as many columns per launch as its input fits in LDS
+int alu_projection(d3_ctx* c, GemvArgs g, int first, int count, int mode, bool norm, hipStream_t s) {
+    const int per = (int)gemv_alu_max_cols(g.K, c->desc.weight_dtype);
+    const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
+    for (int c0 = 0; c0 < count; c0 += per) {
+        GemvArgs h = g;
+        h.x = g.x + (size_t)(first + c0) * g.x_stride;
+        h.out = g.out + (size_t)(first + c0) * g.out_stride;
+        h.ncols = count - c0 < per ? count - c0 : per;
+        h.col0 = first + c0;
+        h.head_start = c->gemv_head_start;
+        int rc = launch_gemv_alu(h, c->desc.weight_dtype, mode, norm, n_wg, s);
+        if (rc != 0) return rc;
+    }
+    return 0;
+}
+
 // One pass of `ncols` columns through the listed blocks.  hidden_dump (or NULL): dev
 // [(n_ids+1)][dump_cols][d], fed from columns [dump_first, dump_first + dump_cols).
+// save_before >= 0: the residual that enters the first listed block >= save_before (the one after the last, if none)
+// is copied to the workspace's h_skip: it is what the blocks of the drop window would have seen.
 int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_t* ids, int n_ids,
-            float* hidden_dump, int dump_first, int dump_cols, const HeadOut* head, hipStream_t s) {
+            float* hidden_dump, int dump_first, int dump_cols, const HeadOut* head, hipStream_t s, int save_before = -1) {
     const d3_model_desc& d = c->desc;
     const int dm = d.d_model, hd = d.head_dim, qdim = d.n_heads * hd, kvdim = d.n_kv_heads * hd, qkv_dim = qdim + 2 * kvdim, F = d.d_ffn;
     float* x = c->at<float>(c->lay.x);
@@ -315,21 +339,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     };
     D3_HIP(dump(0));
 
-    // ALU path: a projection takes as many columns per launch as its input fits in LDS
-    auto alu = [&](GemvArgs g, int first, int count, int mode, bool norm) -> int {
-        const int per = (int)gemv_alu_max_cols(g.K, d.weight_dtype);
-        for (int c0 = 0; c0 < count; c0 += per) {
-            GemvArgs h = g;
-            h.x = g.x + (size_t)(first + c0) * g.x_stride;
-            h.out = g.out + (size_t)(first + c0) * g.out_stride;
-            h.ncols = count - c0 < per ? count - c0 : per;
-            h.col0 = first + c0;
-            h.head_start = c->gemv_head_start;
-            int rc = launch_gemv_alu(h, d.weight_dtype, mode, norm, n_wg, s);
-            if (rc != 0) return rc;
-        }
-        return 0;
-    };
+    auto alu = [&](GemvArgs g, int first, int count, int mode, bool norm) -> int { return alu_projection(c, g, first, count, mode, norm, s); };
 
     int split_len, n_splits;
     pick_splits(c, ncols, cm.pos(ncols - 1) + 1, 2 * c->n_cu, &split_len, &n_splits);
@@ -342,9 +352,15 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     };
     if (mfma) D3_HIP(launch_gain_split(x, dm, gain_after(-1), dm, ncols, n_hi, n_lo, ssq, s));
 
+    bool saved = save_before < 0;
+    auto save_skip = [&]() -> int {
+        saved = true;
+        return (int)hipMemcpyAsync(c->at<float>(c->lay.h_skip), x, (size_t)ncols * dm * sizeof(float), hipMemcpyDeviceToDevice, s);
+    };
     for (int e = 0; e < n_ids; ++e) {
         const int l = ids[e];
         const d3_layer_weights& w = c->layers[l];
+        if (!saved && l >= save_before) D3_HIP(save_skip());
         // --- attention half: x += Wo . attention(RoPE(Wq a), cache) with a = RMSNorm(x) ---
         GemvArgs g{};
         g.K = dm; g.eps = d.rms_eps;
@@ -421,6 +437,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         D3_HIP(dump(e + 1));
     }
 
+    if (!saved) D3_HIP(save_skip());
     if (head) {
         GemvArgs g{};
         g.K = dm; g.eps = d.rms_eps; g.w[0] = c->lm_head; g.rows[0] = d.vocab; g.total_rows = d.vocab;
@@ -521,8 +538,10 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     } else {
         ColMap cm{0, B, 1, ctx->n_ctx};
         HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
+        const bool keep_skip = ctx->fill_mode == D3_FILL_RECOMPUTE && kept < L;
         rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
-                     static_cast<hipStream_t>(hip_stream));
+                     static_cast<hipStream_t>(hip_stream), keep_skip ? ctx->drop_begin[step_i] + (L - kept) : -1);
+        ctx->skip_row = keep_skip && rc == D3_OK ? ctx->n_ctx : -1;
     }
     if (rc != D3_OK) return rc;
     ctx->row_drop_begin[ctx->n_ctx] = ctx->drop_begin[step_i];
@@ -532,13 +551,72 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     return D3_OK;
 }
 
+// RECOMPUTE fill of the row the latest decode step wrote: every dropped block l gets
+// K[l][p] = RoPE(W_k^l a), V[l][p] = W_v^l a with a = RMSNorm_l(h), h = the residual that entered the drop window
+// (kept by that decode step).  One fused launch per dropped block at batch 1 (the QKV kernel without its q heads),
+// three on the matrix-core path (gain split, projection, RoPE + append).
+int fill_recompute(d3_ctx* c, int pos_begin, int pos_end, hipStream_t s) {
+    if (c->fill_mode != D3_FILL_RECOMPUTE)
+        return fail(D3_ESTATE, "d3_fill_missing_kv: RECOMPUTE needs d3_set_fill_mode(ctx, D3_FILL_RECOMPUTE) before the decode step");
+    if (pos_end == pos_begin) return D3_OK;
+    if (pos_end != pos_begin + 1 || pos_begin != c->n_ctx - 1)
+        return fail(D3_ESTATE, "d3_fill_missing_kv: RECOMPUTE fills the row of the latest decode step only (row %d), got [%d, %d)",
+                    c->n_ctx - 1, pos_begin, pos_end);
+    const int p = pos_begin, first = c->row_drop_begin[p], n = c->row_n_drop[p];
+    if (n == 0) return D3_OK;
+    if (c->skip_row != p) return fail(D3_ESTATE, "d3_fill_missing_kv: no kept residual for row %d (written by the prompt pass or the persistent step)", p);
+    const d3_model_desc& d = c->desc;
+    const int dm = d.d_model, hd = d.head_dim, kvdim = d.n_kv_heads * hd, B = c->B;
+    const ColMap cm{0, B, 1, p};
+    const float* h = c->at<float>(c->lay.h_skip);
+    float* kv = c->at<float>(c->lay.qkv);
+    float2* rope_cs = c->at<float2>(c->lay.rope_cs);       // the table of that decode step: same columns, same positions
+    const bool mfma = c->mfma_ok && (B >= 2 || !c->alu_ok);
+    for (int l = first; l < first + n; ++l) {
+        const d3_layer_weights& w = c->layers[l];
+        void* k_layer = c->k_cache + (size_t)l * c->kv_layer_bytes();
+        void* v_layer = c->v_cache + (size_t)l * c->kv_layer_bytes();
+        GemvArgs g{};
+        g.K = dm; g.eps = d.rms_eps; g.w[0] = w.wk; g.w[1] = w.wv; g.rows[0] = kvdim; g.rows[1] = kvdim; g.total_rows = 2 * kvdim;
+        g.out = kv; g.out_stride = 2 * kvdim; g.ncols = B;
+        if (mfma) {
+            bf16_t *n_hi = c->at<bf16_t>(c->lay.n_hi), *n_lo = c->at<bf16_t>(c->lay.n_lo);
+            float* ssq = c->at<float>(c->lay.ssq);
+            D3_HIP(launch_gain_split(h, dm, static_cast<const float*>(w.attn_norm), dm, B, n_hi, n_lo, ssq, s));
+            g.x_hi = n_hi; g.x_lo = n_lo; g.x_stride = dm; g.ssq_in = ssq; g.ssq_parts = 1;
+            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+            RopeArgs r{};
+            r.qkv = kv; r.k_cache = k_layer; r.v_cache = v_layer; r.rope_cs = rope_cs;
+            r.cm = cm; r.ncols = B; r.H = 0; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
+            D3_HIP(launch_rope_append(r, d.kv_dtype, s));
+        } else {
+            g.x = h; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
+            g.rope_cs = rope_cs; g.k_cache = k_layer; g.v_cache = v_layer; g.cm = cm;
+            g.H = 0; g.H_kv = d.n_kv_heads; g.hd = hd; g.max_seq = d.max_seq; g.kv_dtype = d.kv_dtype;
+            D3_HIP(alu_projection(c, g, 0, B, MODE_QKV_ROPE, true, s));
+        }
+    }
+    return D3_OK;
+}
+
+extern "C" int d3_set_fill_mode(d3_ctx* ctx, int32_t mode) {
+    if (!ctx) return fail(D3_EINVAL, "d3_set_fill_mode: ctx is NULL");
+    if (mode != D3_FILL_COPY && mode != D3_FILL_RECOMPUTE) return fail(D3_EINVAL, "d3_set_fill_mode: unknown mode %d", mode);
+    if (mode == D3_FILL_RECOMPUTE && ctx->mega_ok)
+        return fail(D3_ESTATE, "d3_set_fill_mode: RECOMPUTE is not available with the persistent decode step");
+    ctx->fill_mode = mode;
+    ctx->skip_row = -1;
+    return D3_OK;
+}
+
 extern "C" int d3_fill_missing_kv(d3_ctx* ctx, int32_t pos_begin, int32_t pos_end, int32_t mode, void* hip_stream) {
     if (!ctx) return fail(D3_EINVAL, "d3_fill_missing_kv: ctx is NULL");
-    if (mode != D3_FILL_COPY) return fail(D3_EINVAL, "d3_fill_missing_kv: unknown mode %d", mode);
+    if (mode != D3_FILL_COPY && mode != D3_FILL_RECOMPUTE) return fail(D3_EINVAL, "d3_fill_missing_kv: unknown mode %d", mode);
     if (pos_begin < 0 || pos_end < pos_begin || pos_end > ctx->n_ctx)
         return fail(D3_ERANGE, "d3_fill_missing_kv: rows [%d, %d) are outside the %d rows written", pos_begin, pos_end, ctx->n_ctx);
     const d3_model_desc& d = ctx->desc;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (mode == D3_FILL_RECOMPUTE) return fill_recompute(ctx, pos_begin, pos_end, s);
     // consecutive rows whose steps dropped the same window share one launch
     for (int p = pos_begin; p < pos_end;) {
         int q = p + 1;
@@ -564,6 +642,7 @@ extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
     if (n_rows < 1 || n_rows > ctx->n_ctx) return fail(D3_ERANGE, "d3_truncate: n_rows must be in [1, %d] (got %d)", ctx->n_ctx, n_rows);
     ctx->n_ctx = n_rows;
     ctx->last_step = 0;
+    ctx->skip_row = -1;
     return D3_OK;
 }
 

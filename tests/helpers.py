@@ -20,7 +20,8 @@ def oracle_threads() -> int:
 
 def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced: Optional[np.ndarray] = None,
                  kv_dtype: Optional[str] = None, max_seq: Optional[int] = None, min_keep: int = 0, fill_each_step: bool = False,
-                 decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None, persistent: Optional[bool] = None):
+                 decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None, persistent: Optional[bool] = None,
+                 fill_mode: int = 0):
     """Prompt pass + G-1 decode steps through the C ABI.  forced: [B][G-1] tokens fed instead of the GPU's own.
     Returns dict(tokens [G][B], logits [G][B][V], hidden: list of [(k_i+1)][B][d], decoder)."""
     import torch
@@ -45,6 +46,7 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
     L = shape.L
     keep, _, _ = binding.d3_plan_depth(L, alpha, start, min_keep, max(G, 2))
     decoder.set_plan(alpha, start, min_keep, max(G, 2))
+    decoder.set_fill_mode(fill_mode)
     toks = torch.from_numpy(np.ascontiguousarray(prompts, np.int32)).to(dev)
     logits = torch.zeros(B, shape.V, dtype=torch.float32, device=dev)
     hid = torch.zeros(L + 1, B, shape.d, dtype=torch.float32, device=dev)
@@ -60,7 +62,7 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
         hid_i = torch.zeros(k + 1, B, shape.d, dtype=torch.float32, device=dev)
         decoder.decode_step(cur, i, nxt, logits=logits, hidden_dump=hid_i)
         if fill_each_step:
-            decoder.fill_missing_kv(decoder.n_ctx - 1, decoder.n_ctx)
+            decoder.fill_missing_kv(decoder.n_ctx - 1, decoder.n_ctx, fill_mode)
         cur = nxt.clone()
         out_tokens.append(cur.cpu().numpy().copy())
         out_logits.append(logits.cpu().numpy().copy())

@@ -150,3 +150,102 @@ def test_decode_is_deterministic_and_rewind_reproduces_it():
         runs.append(rec)
     for (t0, l0), (t1, l1) in zip(*runs):
         assert (t0 == t1).all() and (l0 == l1).all()                              # bit-identical replays
+
+
+def _check_recomputed_rows(dec, gens, shape, P, G, tol):
+    L = shape.L
+    worst = 0.0
+    for b, gen in enumerate(gens):
+        oracle.fill_generated_rows(gen, P, G, mode="recompute")
+        for i in range(1, G):
+            pos = P + i - 1
+            s, n = int(gen.drop_begin[i]), L - int(gen.keep[i])
+            for l in range(s, s + n):
+                kg, vg = _cache_rows(dec, l, b, pos)
+                ko, vo = gen.seq.get_kv(l, pos)
+                ek = np.abs(kg - ko).max() / max(1.0, np.abs(ko).max())
+                ev = np.abs(vg - vo).max() / max(1.0, np.abs(vo).max())
+                worst = max(worst, ek, ev)
+                assert ek <= tol and ev <= tol, f"seq {b} step {i} block {l}: K {ek:.3e} V {ev:.3e}"
+    return worst
+
+
+@pytest.mark.parametrize("B,start,kv", [(1, 2, "f16"), (1, 0, "f32"), (3, 2, "f16"), (3, 4, "bf16"), (2, 0, "f16")])
+def test_recompute_fill_matches_oracle_and_continuation_reads_it(B, start, kv):
+    """RECOMPUTE fill: K/V of every dropped block recomputed from the hidden state copied through the drop window
+    (batch 1: the fused QKV kernel without q heads; batch >= 2: the matrix-core path), then a second request on the
+    same cache at full depth reads the recomputed rows."""
+    import torch
+    from paper_2503_08524_amd import binding
+    shape, P, G, alpha = SHAPE, 6, 9, 0.8
+    P2, G2 = 4, 4
+    w = d3_inputs.make_weights(shape, 2)
+    prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)
+    prompts2 = d3_inputs.make_prompt(B, P2, shape.V, seed=5)
+    forced2 = d3_inputs.make_prompt(B, G2 - 1, shape.V, seed=6)
+    max_seq = P + G + P2 + G2
+    print(f"case recompute fill B={B} start={start} kv={kv}", flush=True)
+    gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, kv_dtype=kv, fill_each_step=True,
+                               max_seq=max_seq, fill_mode=binding.D3_FILL_RECOMPUTE)
+    dec = gpu["decoder"]
+    torch.cuda.synchronize()
+    model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq)
+    tol = {"f32": 5e-5, "f16": 4e-3, "bf16": 3e-2}[kv]
+    worst = _check_recomputed_rows(dec, gens, shape, P, G, tol)
+    n_rows = P + G - 1
+    gpu2 = helpers.gpu_generate(shape, w, prompts2, G2, alpha, start, forced=forced2, decoder=dec, pos_begin=n_rows)
+    gens2 = [oracle.generate(model, prompts2[b], G2, alpha, start, seq=gen.seq, pos_begin=n_rows, forced=forced2[b])
+             for b, gen in enumerate(gens)]
+    wl, wh = helpers.compare(gpu2, gens2, G2)
+    print(f"  worst recomputed row err {worst:.3e}; continuation logit abs err {wl:.3e}, hidden {wh:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("name,B", [("llama-7b", 1), ("llama-70b", 2)])
+def test_recompute_fill_at_real_widths(name, B):
+    import torch
+    from paper_2503_08524_amd import binding
+    shape = d3_inputs.SHAPES[name].truncated(3)
+    P, G, alpha, start = 24, 4, 0.6, 1                  # keeps 3, 1, 1, 0 blocks: windows [1,3), [1,3), [0,3)
+    w = d3_inputs.make_weights(shape, 0)
+    prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)
+    print(f"case recompute fill {shape.name} B={B}", flush=True)
+    gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, fill_each_step=True,
+                               fill_mode=binding.D3_FILL_RECOMPUTE)
+    torch.cuda.synchronize()
+    model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced)
+    assert [int(k) for k in gens[0].keep[:G]] == [3, 1, 1, 0]
+    worst = _check_recomputed_rows(gpu["decoder"], gens, shape, P, G, 4e-3)
+    print(f"  worst recomputed row err {worst:.3e}", flush=True)
+
+
+def test_recompute_fill_call_rules():
+    import torch
+    from paper_2503_08524_amd import binding, D3Error
+    shape = SHAPE
+    w = binding.weights_to_device(shape, d3_inputs.make_weights(shape, 2))
+    dec = binding.Decoder(shape, w, 2, 16)
+    prompts = torch.from_numpy(d3_inputs.make_prompt(2, 6, shape.V, seed=1)).to("cuda:0")
+    tok = torch.zeros(2, dtype=torch.int32, device="cuda:0")
+    out = torch.zeros_like(tok)
+
+    def status(fn):
+        with pytest.raises(D3Error) as e:
+            fn()
+        return e.value.status
+
+    dec.set_plan(0.7, 2, 0, 6)
+    dec.prefill(prompts)
+    dec.decode_step(tok, 1, out)
+    assert status(lambda: dec.fill_missing_kv(6, 7, binding.D3_FILL_RECOMPUTE)) == -4    # mode was not declared before the step
+    assert status(lambda: dec.set_fill_mode(7)) == -1
+    dec.set_fill_mode(binding.D3_FILL_RECOMPUTE)
+    assert status(lambda: dec.fill_missing_kv(6, 7, binding.D3_FILL_RECOMPUTE)) == -4    # that step kept no residual
+    dec.decode_step(tok, 2, out)
+    assert status(lambda: dec.fill_missing_kv(6, 8, binding.D3_FILL_RECOMPUTE)) == -4    # only the latest row
+    assert status(lambda: dec.fill_missing_kv(6, 7, binding.D3_FILL_RECOMPUTE)) == -4
+    dec.fill_missing_kv(7, 8, binding.D3_FILL_RECOMPUTE)
+    dec.fill_missing_kv(6, 7, binding.D3_FILL_COPY)                                     # COPY stays available for any row
+    dec.sync_check()
+    dec.close()

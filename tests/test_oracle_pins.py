@@ -262,3 +262,44 @@ def test_first_block_cache_write_alone_equals_the_full_forward():
             assert np.array_equal(kf, ko) and np.array_equal(vf, vo)
             k3, v3 = only.get_kv(3, p)
             assert not k3.any() and not v3.any()          # no other block's row was touched
+
+
+@pytest.mark.parametrize("shape,alpha,start", [(MICRO, "0.8", 2), (MICRO_GQA, "0.85", 0), (MICRO, "0.9", 4)])
+def test_recompute_fill_definition_and_continuation_match_brute_force(shape, alpha, start):
+    """RECOMPUTE fill (Section 3.2: copied hidden state, recomputed KV).  Definitional pin: the first block of a drop
+    window sees exactly the copied state, so its recomputed row equals, bit for bit, the row the same block writes when
+    it is executed right after the same predecessors.  Whole-path pin: a second request on the filled cache runs full
+    depth and reads every filled row; the NumPy brute force (no cache, its own recompute code) must agree."""
+    w, w64, model = _setup(shape, seed=5)
+    L = shape.L
+    P, G, P2, G2 = 5, 6, 3, 3
+    prompt = d3_inputs.make_prompt(1, P, shape.V, seed=4)[0]
+    gen = oracle.generate(model, prompt, G, float(alpha), start, max_seq=P + G + P2 + G2)
+    oracle.fill_generated_rows(gen, P, G, mode="recompute")
+    row_blocks = [list(range(L))] * P
+    for i in range(1, G):
+        pos, s, n = P + i - 1, int(gen.drop_begin[i]), int(L - gen.keep[i])
+        row_blocks.append(bruteforce.executed_blocks(L, alpha, start, i))
+        if n == 0:
+            continue
+        # a fresh cache with the same earlier rows, where row pos runs the predecessors AND block s
+        ref = model.new_seq(P + G)
+        for t in range(pos):
+            fed = int(prompt[t]) if t < P else gen.fed[t - P]
+            ref.forward_token(fed, t, row_blocks[t])
+        ref.forward_token(gen.fed[i - 1], pos, [l for l in range(L) if l < s] + [s])
+        kr, vr = ref.get_kv(s, pos)
+        kf, vf = gen.seq.get_kv(s, pos)
+        assert np.array_equal(kr, kf) and np.array_equal(vr, vf)
+        if n > 1:                                    # deeper blocks of the window see the copied state, not block s's output
+            assert not np.array_equal(gen.seq.get_kv(s + 1, pos)[0], kf)
+    prompt2 = d3_inputs.make_prompt(1, P2, shape.V, seed=9)[0]
+    gen2 = oracle.generate(model, prompt2, G2, float(alpha), start, seq=gen.seq, pos_begin=P + G - 1)
+    tokens = list(prompt) + gen.tokens[:G - 1] + list(prompt2)
+    row_blocks += [list(range(L))] * P2
+    for i in range(G2):
+        if i >= 1:
+            tokens.append(gen2.tokens[i - 1])
+            row_blocks.append(bruteforce.executed_blocks(L, alpha, start, i))
+        logits, _ = bruteforce.forward_all(shape, w64, tokens, row_blocks, fill="recompute")
+        np.testing.assert_allclose(gen2.logits[i], logits, rtol=0, atol=1e-11)

@@ -62,6 +62,107 @@ struct AttnShared {
     int is_last;
 };
 
+// Second half of a split (all waves have put their running max, sum and unnormalised output of every head
+// into `sh` and passed a barrier): merge the waves, publish the split's partial of every head, and let the
+// split that arrives last at the (column, KV head) counter merge all splits and write the output.
+template <int HD, bool FUSED, int NW, int G>
+__device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split, int h0, int c, int n_live, AttnShared<HD, NW, G>& sh) {
+    const int tid = threadIdx.x;
+    // ---- merge the waves; publish this split's partial of every head ----
+    for (int idx = tid; idx < G * HD; idx += NW * 64) {
+        const int g = idx / HD, t = idx % HD;
+        float M = sh.m[g][0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sh.m[g][w]);
+        float L = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = sh.m[g][w] > -INFINITY ? exp2f(sh.m[g][w] - M) : 0.f;
+            L += sh.l[g][w] * f;
+            o += sh.o[g][w][t] * f;
+        }
+        if (n_live == 1) {                             // the only split of this column: the result is final
+            const float r = o / L;
+            const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
+            if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
+            if (a.out_hi) {
+                const uint32_t hb = f32_to_bf16(r);
+                a.out_hi[oi] = (bf16_t)hb;
+                a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+            }
+            continue;
+        }
+        const size_t pidx = ((size_t)c * a.H + h0 + g) * a.n_splits + split;
+        st_agent(&a.part_o[pidx * HD + t], o);
+        if (t == 0) { st_agent(&a.part_ml[pidx * 2], M); st_agent(&a.part_ml[pidx * 2 + 1], L); }
+    }
+
+    if (n_live == 1) return;
+    // ---- the split that arrives last merges all splits of this (column, KV head) ----
+    wait_stores();                                     // this split's partials have reached the coherence point
+    __syncthreads();
+    if (tid == 0) {
+        int* ticket = &a.tickets[c * a.H + h0];          // one counter per head group, indexed by its first query head
+        const int done = atomicAdd(ticket, 1);
+        sh.is_last = done == n_live - 1;
+        if (sh.is_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
+    }
+    __syncthreads();
+    if (!sh.is_last) return;
+    // every thread owns ITEMS (head, element) outputs; the partials of all of them are fetched together, in rounds
+    // of 8 splits (one round trip per round), and merged with a running max
+    constexpr int ITEMS = (G * HD + NW * 64 - 1) / (NW * 64);
+    float gm[ITEMS], L[ITEMS], o[ITEMS];
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) { gm[i] = -INFINITY; L[i] = 0.f; o[i] = 0.f; }
+    for (int s0 = 0; s0 < n_live; s0 += 8) {
+        float ms[ITEMS][8], ls[ITEMS][8], os[ITEMS][8];
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            int idx = tid + i * (NW * 64);
+            idx = idx < G * HD ? idx : G * HD - 1;
+            const size_t p0 = ((size_t)c * a.H + h0 + idx / HD) * a.n_splits;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
+                ms[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
+                ls[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
+                os[i][k] = ld_agent(&a.part_o[(p0 + sidx) * HD + idx % HD]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < ITEMS; ++i) {
+            float rm = gm[i];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[i][k]);
+            const float keep = exp2f(gm[i] - rm);         // -inf on the first round: exp2(-inf) = 0
+            L[i] *= keep; o[i] *= keep;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                if (s0 + k < n_live) {
+                    const float w = exp2f(ms[i][k] - rm);
+                    L[i] += ls[i][k] * w;
+                    o[i] += os[i][k] * w;
+                }
+            }
+            gm[i] = rm;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < ITEMS; ++i) {
+        const int idx = tid + i * (NW * 64);
+        if (idx >= G * HD) continue;
+        const float r = o[i] / L[i];
+        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + idx / HD) * HD + idx % HD;
+        if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
+        if (a.out_hi) {
+            const uint32_t hb = f32_to_bf16(r);
+            a.out_hi[oi] = (bf16_t)hb;
+            a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+        }
+    }
+}
+
 // One (column, KV head, context split) per call by a workgroup of NW waves, for the G query heads
 // h0 .. h0+G-1 that share that KV head (G = 1: plain multi-head attention, or a group size the
 // kernel is not instantiated for, handled one query head at a time).  Every cache row of the split is
@@ -276,99 +377,223 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     }
     __syncthreads();
 
-    // ---- merge the waves; publish this split's partial of every head ----
-    for (int idx = tid; idx < G * HD; idx += NW * 64) {
-        const int g = idx / HD, t = idx % HD;
-        float M = sh.m[g][0];
+    attn_merge_publish<HD, FUSED, NW, G>(a, split, h0, c, n_live, sh);
+}
+
+// ---------------- grouped-query decode attention on the matrix cores ----------------
+// With G query heads per KV head the vector-ALU kernel above does G times the arithmetic per cache byte
+// and is bound by it (G = 8: 33 us for 34 MB at the 70B shape).  Here both contractions run as
+// v_mfma_f32_16x16x32_f16 with the heads of the group (padded to 16) as one matrix dimension; fp16 cache,
+// head_dim 128.  A wave takes 32 cache rows at a time:
+//   scores^T [row][head] = K [row][hd] . q^T [hd][head]: A = a 16-row K tile (coalesced load, re-shaped through
+//     LDS into fragments), B = q (scaled, split hi + lo in fp16): the result leaves lane (i, g) with head i,
+//     rows 4g..4g+3 of the tile; two tiles give each lane 8 of the 32 rows of its head;
+//   online softmax per head in that layout (max / sum across the 4 lanes of a head by shuffles);
+//   out [head][col] += P [head][row] . V [row][col]: A = P (hi + lo in fp16), whose 8 rows per lane are exactly an A
+//     fragment under the row numbering k = 8g + j <-> row 4g + j (j < 4), 16 + 4g + j - 4 (j >= 4);
+//     B = V read from its LDS tile in the same numbering (eight 2-byte reads per fragment: V's contraction
+//     index is the row, which is the slow index of the cache).
+// The waves' states go through the same LDS merge, split partials and arrival counter as above.
+typedef _Float16 attn_half8 __attribute__((ext_vector_type(8)));
+typedef float attn_f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kAttnPitch = 272;            // bytes per staged row of 128 halves (+16: conflict-free fragment reads)
+
+template <int NW, int G>
+struct AttnMfmaShared {
+    union {
+        struct {
+            char k[NW][16 * kAttnPitch];   // one K tile per wave
+            char v[NW][32 * kAttnPitch];   // one 32-row V tile per wave
+            float keep[NW][16];            // rescale factor of each head, from the score layout to the output layout
+        } stage;
+        AttnShared<128, NW, G> merge;
+    };
+};
+
+template <bool ROPE, int NW, int G>
+__device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, int h0, int c, AttnMfmaShared<NW, G>& sh) {
+    constexpr int HD = 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
+    const int j0 = split * a.split_len;
+    const int j1 = min(j0 + a.split_len, ctx);
+    if (j0 >= j1) return;
+    const bool has_new = ROPE && j1 == ctx;            // the newest row is patched into the staged tiles, not read from the cache
+    const int n_live = (ctx + a.split_len - 1) / a.split_len;
+    const int kvh = h0 / (a.H / a.H_kv);
+    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
+    const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
+    const float scale = 1.4426950408889634f / sqrtf((float)HD);      // scores in log2 units
+
+    // ---- q as the B operand: lane (i, g) holds q[h0 + i][32 kk + 8 g .. + 8], kk = 0..3, scaled, hi + lo ----
+    attn_half8 qhi[4], qlo[4];
+    {
+        float qf[4][8];
 #pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, sh.m[g][w]);
-        float L = 0.f, o = 0.f;
+        for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            const float f = sh.m[g][w] > -INFINITY ? exp2f(sh.m[g][w] - M) : 0.f;
-            L += sh.l[g][w] * f;
-            o += sh.o[g][w][t] * f;
-        }
-        if (n_live == 1) {                             // the only split of this column: the result is final
-            const float r = o / L;
-            const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
-            if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
-            if (a.out_hi) {
-                const uint32_t hb = f32_to_bf16(r);
-                a.out_hi[oi] = (bf16_t)hb;
-                a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+            for (int e = 0; e < 8; ++e) qf[kk][e] = 0.f;
+        if (i < G) {
+            const float* qp = a.q + (size_t)c * a.q_stride + (size_t)(h0 + i) * HD + 8 * g;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const float4 t0 = *reinterpret_cast<const float4*>(qp + 32 * kk), t1 = *reinterpret_cast<const float4*>(qp + 32 * kk + 4);
+                qf[kk][0] = t0.x; qf[kk][1] = t0.y; qf[kk][2] = t0.z; qf[kk][3] = t0.w;
+                qf[kk][4] = t1.x; qf[kk][5] = t1.y; qf[kk][6] = t1.z; qf[kk][7] = t1.w;
             }
-            continue;
+            if (ROPE) {                                // dims d and d + 64 are the same (g, e) of fragments kk and kk + 2
+                const float2* cs = a.rope_cs + (size_t)c * (HD / 2) + 8 * g;
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int e = 0; e < 8; e += 2) {
+                        const float4 t = *reinterpret_cast<const float4*>(cs + 32 * kk + e);
+                        const float x0 = qf[kk][e], x1 = qf[kk + 2][e], z0 = qf[kk][e + 1], z1 = qf[kk + 2][e + 1];
+                        qf[kk][e] = x0 * t.x - x1 * t.y;         qf[kk + 2][e] = x0 * t.y + x1 * t.x;
+                        qf[kk][e + 1] = z0 * t.z - z1 * t.w;     qf[kk + 2][e + 1] = z0 * t.w + z1 * t.z;
+                    }
+            }
         }
-        const size_t pidx = ((size_t)c * a.H + h0 + g) * a.n_splits + split;
-        st_agent(&a.part_o[pidx * HD + t], o);
-        if (t == 0) { st_agent(&a.part_ml[pidx * 2], M); st_agent(&a.part_ml[pidx * 2 + 1], L); }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = qf[kk][e] * scale;
+                const f16_t h = (f16_t)v;
+                qhi[kk][e] = h;
+                qlo[kk][e] = (f16_t)(v - (float)h);
+            }
     }
 
-    if (n_live == 1) return;
-    // ---- the split that arrives last merges all splits of this (column, KV head) ----
-    wait_stores();                                     // this split's partials have reached the coherence point
-    __syncthreads();
-    if (tid == 0) {
-        int* ticket = &a.tickets[c * a.H + h0];          // one counter per head group, indexed by its first query head
-        const int done = atomicAdd(ticket, 1);
-        sh.is_last = done == n_live - 1;
-        if (sh.is_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
+    // ---- the newest row in the layout of the staged tiles: lane (.., seg = lane % 16) holds dims 8 seg .. + 8 ----
+    attn_half8 nk, nv;
+    if (has_new) {
+        const int seg = lane & 15;
+        const bool upper = seg >= 8;
+        const float* kp = a.q + (size_t)c * a.q_stride + (size_t)(a.H + kvh) * HD + 8 * seg;
+        const float* pp = kp + (upper ? -(HD / 2) : HD / 2);
+        const float* vp = kp + (size_t)a.H_kv * HD;
+        const float2* cs = a.rope_cs + (size_t)c * (HD / 2) + 8 * (seg & 7);
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            const float2 own = *reinterpret_cast<const float2*>(kp + e), par = *reinterpret_cast<const float2*>(pp + e);
+            const float4 t = *reinterpret_cast<const float4*>(cs + e);
+            const float y0 = upper ? par.x * t.y + own.x * t.x : own.x * t.x - par.x * t.y;
+            const float y1 = upper ? par.y * t.w + own.y * t.z : own.y * t.z - par.y * t.w;
+            const float2 vv = *reinterpret_cast<const float2*>(vp + e);
+            nk[e] = (f16_t)fminf(fmaxf(y0, -65504.f), 65504.f);     nk[e + 1] = (f16_t)fminf(fmaxf(y1, -65504.f), 65504.f);
+            nv[e] = (f16_t)fminf(fmaxf(vv.x, -65504.f), 65504.f);   nv[e + 1] = (f16_t)fminf(fmaxf(vv.y, -65504.f), 65504.f);
+        }
+        if (wave == 0 && lane < 16) {                  // one copy of the row goes to the cache (the caches are this launch's to extend)
+            *reinterpret_cast<attn_half8*>(const_cast<f16_t*>(Kb) + (size_t)(ctx - 1) * HD + 8 * seg) = nk;
+            *reinterpret_cast<attn_half8*>(const_cast<f16_t*>(Vb) + (size_t)(ctx - 1) * HD + 8 * seg) = nv;
+        }
     }
-    __syncthreads();
-    if (!sh.is_last) return;
-    // every thread owns ITEMS (head, element) outputs; the partials of all of them are fetched together, in rounds
-    // of 8 splits (one round trip per round), and merged with a running max
-    constexpr int ITEMS = (G * HD + NW * 64 - 1) / (NW * 64);
-    float gm[ITEMS], L[ITEMS], o[ITEMS];
+
+    // ---- running state: score layout (lane = head i; the four g lanes of a head agree on m) and output layout ----
+    float m = -INFINITY, lsum = 0.f;
+    attn_f32x4 acc[8];                                 // [column tile nt]: lane (i, g) holds column 16 nt + i, heads 4g..4g+3
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) { gm[i] = -INFINITY; L[i] = 0.f; o[i] = 0.f; }
-    for (int s0 = 0; s0 < n_live; s0 += 8) {
-        float ms[ITEMS][8], ls[ITEMS][8], os[ITEMS][8];
+    for (int nt = 0; nt < 8; ++nt) acc[nt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+    char* kbuf = sh.stage.k[wave];
+    char* vbuf = sh.stage.v[wave];
+    float* keepbuf = sh.stage.keep[wave];
+    const int lrow = lane >> 4, lseg = lane & 15;      // coalesced loads: 16 lanes read 256 contiguous bytes of one row
+
+    for (int r0 = j0 + wave * 32; r0 < j1; r0 += NW * 32) {
+        uint4 kreg[2][4], vreg[8];
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            int idx = tid + i * (NW * 64);
-            idx = idx < G * HD ? idx : G * HD - 1;
-            const size_t p0 = ((size_t)c * a.H + h0 + idx / HD) * a.n_splits;
+        for (int q = 0; q < 8; ++q) {
+            int row = r0 + 4 * q + lrow;
+            row = row < j1 ? row : j1 - 1;
+            kreg[q >> 2][q & 3] = __builtin_bit_cast(uint4, load_stream16(Kb + (size_t)row * HD + 8 * lseg));
+            vreg[q] = __builtin_bit_cast(uint4, load_stream16(Vb + (size_t)row * HD + 8 * lseg));
+        }
+        // ---- scores^T of the two K tiles ----
+        attn_f32x4 S[2];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
-                ms[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
-                ls[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
-                os[i][k] = ld_agent(&a.part_o[(p0 + sidx) * HD + idx % HD]);
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<uint4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[t][q];
+            if (has_new && ctx - 1 >= r0 + 16 * t && ctx - 1 < r0 + 16 * t + 16 && lane < 16)
+                *reinterpret_cast<attn_half8*>(kbuf + (ctx - 1 - r0 - 16 * t) * kAttnPitch + lseg * 16) = nk;
+            __builtin_amdgcn_wave_barrier();
+            S[t] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf + i * kAttnPitch + kk * 64 + g * 16);
+                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qhi[kk], S[t], 0, 0, 0);
+                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qlo[kk], S[t], 0, 0, 0);
             }
+            __builtin_amdgcn_wave_barrier();
         }
+        // ---- online softmax of head i over this lane's 8 rows and the other three lanes of the head ----
+        float mx = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < ITEMS; ++i) {
-            float rm = gm[i];
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[i][k]);
-            const float keep = exp2f(gm[i] - rm);         // -inf on the first round: exp2(-inf) = 0
-            L[i] *= keep; o[i] *= keep;
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                if (s0 + k < n_live) {
-                    const float w = exp2f(ms[i][k] - rm);
-                    L[i] += ls[i][k] * w;
-                    o[i] += os[i][k] * w;
-                }
+            for (int e = 0; e < 4; ++e) {
+                if (r0 + 16 * t + 4 * g + e >= j1) S[t][e] = -INFINITY;
+                mx = fmaxf(mx, S[t][e]);
             }
-            gm[i] = rm;
-        }
-    }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));        // finite: row r0 is valid
+        const float m_new = fmaxf(m, mx);
+        const float keep = exp2f(m - m_new);           // exp2(-inf) = 0 the first time
+        attn_half8 phi, plo;
+        float ps = 0.f;
 #pragma unroll
-    for (int i = 0; i < ITEMS; ++i) {
-        const int idx = tid + i * (NW * 64);
-        if (idx >= G * HD) continue;
-        const float r = o[i] / L[i];
-        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + idx / HD) * HD + idx % HD;
-        if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
-        if (a.out_hi) {
-            const uint32_t hb = f32_to_bf16(r);
-            a.out_hi[oi] = (bf16_t)hb;
-            a.out_lo[oi] = (bf16_t)f32_to_bf16(r - bf16_to_f32(hb));
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p = exp2f(S[t][e] - m_new);
+                ps += p;
+                const f16_t h = (f16_t)p;
+                phi[4 * t + e] = h;
+                plo[4 * t + e] = (f16_t)(p - (float)h);
+            }
+        lsum = lsum * keep + ps;
+        m = m_new;
+        // ---- the heads' rescale factors, from lane = head to lane (column, heads 4g..4g+3) ----
+        if (g == 0) keepbuf[i] = keep;
+        // ---- V tile ----
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<uint4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
+        if (has_new && ctx - 1 >= r0 && ctx - 1 < r0 + 32 && lane < 16)
+            *reinterpret_cast<attn_half8*>(vbuf + (ctx - 1 - r0) * kAttnPitch + lseg * 16) = nv;
+        __builtin_amdgcn_wave_barrier();
+        const float4 kf = *reinterpret_cast<const float4*>(keepbuf + 4 * g);
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
+            attn_half8 vb;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4);
+                vb[j] = *reinterpret_cast<const f16_t*>(vbuf + row * kAttnPitch + (16 * nt + i) * 2);
+            }
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
         }
+        __builtin_amdgcn_wave_barrier();               // the tiles are free for the next 32 rows
     }
+
+    // ---- waves -> LDS (the staging tiles give way to the merge area), then the common second half ----
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (4 * g + e < G) sh.merge.o[4 * g + e][wave][16 * nt + i] = acc[nt][e];
+    if (g == 0 && i < G) { sh.merge.m[i][wave] = m; sh.merge.l[i][wave] = lsum; }
+    __syncthreads();
+    attn_merge_publish<128, false, NW, G>(a, split, h0, c, n_live, sh.merge);
 }
 
 }  // namespace d3

@@ -6,6 +6,9 @@
 // 16 bytes per lane, several rows per wave per load, once for all query heads of a KV head;
 // every wave keeps an online softmax per head in registers; reductions are wave shuffles plus
 // one LDS hop across the four waves.
+#include <cstdlib>
+#include <type_traits>
+
 #include "attention.h"
 
 namespace d3 {
@@ -19,9 +22,29 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     attn_split<T, HD, false, 4, G, ROPE>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
 }
 
+template <int G, bool ROPE>
+__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
+    __shared__ AttnMfmaShared<4, G> sh;
+    attn_split_mfma<ROPE, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
+}
+
+// D3_ATTN_MFMA=0 keeps grouped-query attention on the vector ALUs (for comparisons)
+bool attn_mfma_enabled() {
+    static const bool on = [] { const char* e = getenv("D3_ATTN_MFMA"); return !(e && e[0] == '0'); }();
+    return on;
+}
+
 template <typename T, int HD, bool ROPE>
 int launch_g(const AttnArgs& a, hipStream_t s) {
     const int group = a.H / a.H_kv;
+    if constexpr (std::is_same<T, f16_t>::value && HD == 128) {
+        if ((group == 4 || group == 8) && attn_mfma_enabled()) {
+            dim3 grid(a.n_splits, a.H / group, a.ncols);
+            if (group == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, ROPE>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((attn_mfma_kernel<4, ROPE>), grid, dim3(256), 0, s, a);
+            return (int)hipGetLastError();
+        }
+    }
     const int g = (group == 2 || group == 4 || group == 8) ? group : 1;    // other group sizes: one query head per workgroup
     dim3 grid(a.n_splits, a.H / g, a.ncols);
     if (g == 8) hipLaunchKernelGGL((attn_kernel<T, HD, 8, ROPE>), grid, dim3(256), 0, s, a);

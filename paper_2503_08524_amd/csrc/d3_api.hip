@@ -321,7 +321,6 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     bf16_t *s_hi = c->at<bf16_t>(c->lay.s_hi), *s_lo = c->at<bf16_t>(c->lay.s_lo);
     bf16_t *f_hi = c->at<bf16_t>(c->lay.f_hi), *f_lo = c->at<bf16_t>(c->lay.f_lo);
     const bool mfma = c->mfma_ok && (ncols >= 2 || !c->alu_ok);
-    const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
     // a decode pass (every column a different sequence) on the matrix-core path leaves the rotary embedding and the
     // cache append to the attention kernel; a prompt chunk holds several positions of one sequence and needs the
     // rows in the cache before attention starts

@@ -295,7 +295,7 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* 
     // chip, within the register budget; stacked matrices must not share a workgroup
     // (rows[m] % (16 RT) == 0).
     int best_rt = 1, best_waves = 4;
-    const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave
+    const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave (more spills: measured 1.5-2.5x slower)
     const int rt_forced = env_int("D3_MFMA_RT", 1, 4), waves_forced = env_int("D3_MFMA_WAVES", 1, 8);
     for (int rt = rt_max; rt >= 1; rt /= 2) {
         if (tiles % rt != 0) continue;

@@ -12,7 +12,7 @@ untimed; each step rewinds the cache to the prompt with d3_truncate.  `value` is
 tokens/s at alpha = 0.995; full depth (alpha = 1) and alpha = 0.99 are reported beside it,
 each with its algorithmic HBM bytes per token and fraction of the 8 TB/s peak.
 
-python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny]
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny|7b-long] [--fill copy|recompute|none]
 """
 from __future__ import annotations
 
@@ -39,6 +39,9 @@ CONFIGS = {
     "13b": (d3_inputs.LLAMA_13B, 4, 1024, 256, (0.995, 1.0), 0.6),
     "7b-b32": (d3_inputs.LLAMA_7B, 32, 2048, 512, (0.995, 1.0), 0.6),
     "70b": (d3_inputs.LLAMA_70B, 8, 1024, 256, (0.995, 1.0), 0.6),
+    # a long-generation shape beside the benchmark's five: the paper's GSM8K setting (maximum length 1024,
+    # alpha = 0.9999, start = 0.2, batch 4 for the 7B model; Section 4.1 and 4.2)
+    "7b-long": (d3_inputs.LLAMA_7B, 4, 512, 1024, (0.9999, 1.0), 0.2),
 }
 
 

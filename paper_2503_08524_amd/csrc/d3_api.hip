@@ -100,6 +100,7 @@ struct d3_ctx {
     Layout lay;
     int n_cu;
     int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
+    int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU, default 2)
     int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
@@ -176,6 +177,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->n_cu = prop.multiProcessorCount;
     c->gemv_wgs_per_cu = 3;
     c->gemv_head_start = 0;
+    c->attn_wgs_per_cu = 2;
+    if (const char* env = getenv("D3_ATTN_WGS_PER_CU")) { const int v = atoi(env); if (v >= 1 && v <= 16) c->attn_wgs_per_cu = v; }
     if (const char* env = getenv("D3_GEMV_HEAD_START")) { const int v = atoi(env); if (v >= 0 && v <= 64) c->gemv_head_start = v; }
     if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {
         const int v = atoi(env);
@@ -341,7 +344,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     auto alu = [&](GemvArgs g, int first, int count, int mode, bool norm) -> int { return alu_projection(c, g, first, count, mode, norm, s); };
 
     int split_len, n_splits;
-    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, 2 * c->n_cu, &split_len, &n_splits);
+    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, c->attn_wgs_per_cu * c->n_cu, &split_len, &n_splits);
 
     // Matrix-core path: RMSNorm lives inside the projections.  Whoever writes the residual also writes the split of
     // residual * (gain of the norm that reads it next) and partial sums of squares; the reading projection scales its

@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, gemm_part, gemm_tickets, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -84,6 +84,8 @@ Layout make_layout(const d3_model_desc& d) {
     l.n_lo = take(C * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
     l.h_skip = take(C * d.d_model * 4);
+    l.gemm_part = take(kGemmPartBytes);
+    l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
     l.cand_val = take(4096 * 4);
     l.cand_idx = take(4096 * 4);
     l.total = o;
@@ -223,6 +225,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kMaxCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
+    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.gemm_tickets), 0, (size_t)kGemmPartTickets * sizeof(int));
     if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
     return D3_OK;
@@ -365,6 +368,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         if (!saved && l >= save_before) D3_HIP(save_skip());
         // --- attention half: x += Wo . attention(RoPE(Wq a), cache) with a = RMSNorm(x) ---
         GemvArgs g{};
+        g.part = c->at<float>(c->lay.gemm_part); g.part_tickets = c->at<int>(c->lay.gemm_tickets);
         g.K = dm; g.eps = d.rms_eps;
         g.w[0] = w.wq; g.w[1] = w.wk; g.w[2] = w.wv;
         g.rows[0] = qdim; g.rows[1] = kvdim; g.rows[2] = kvdim; g.total_rows = qkv_dim;
@@ -404,6 +408,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         }
 
         GemvArgs o{};
+        o.part = c->at<float>(c->lay.gemm_part); o.part_tickets = c->at<int>(c->lay.gemm_tickets);
         o.K = qdim; o.w[0] = w.wo; o.rows[0] = dm; o.total_rows = dm; o.out = x; o.out_stride = dm; o.ncols = ncols;
         {
             Timed t(c, D3_K_OPROJ, s);
@@ -417,9 +422,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
 
         // --- SwiGLU half: x += Wd (silu(Wg m) * (Wu m)) with m = RMSNorm(x) ---
         GemvArgs u{};
+        u.part = c->at<float>(c->lay.gemm_part); u.part_tickets = c->at<int>(c->lay.gemm_tickets);
         u.K = dm; u.eps = d.rms_eps; u.w[0] = w.w_gate; u.w[1] = w.w_up; u.rows[0] = F; u.rows[1] = F; u.total_rows = F;
         u.out_stride = F; u.ncols = ncols;
         GemvArgs dn{};
+        dn.part = c->at<float>(c->lay.gemm_part); dn.part_tickets = c->at<int>(c->lay.gemm_tickets);
         dn.K = F; dn.w[0] = w.w_down; dn.rows[0] = dm; dn.total_rows = dm; dn.out = x; dn.out_stride = dm; dn.ncols = ncols;
         if (mfma) {
             u.x_hi = n_hi; u.x_lo = n_lo; u.x_stride = dm; u.ssq_in = ssq; u.ssq_parts = ssq_parts;
@@ -442,6 +449,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     if (!saved) D3_HIP(save_skip());
     if (head) {
         GemvArgs g{};
+        g.part = c->at<float>(c->lay.gemm_part); g.part_tickets = c->at<int>(c->lay.gemm_tickets);
         g.K = dm; g.eps = d.rms_eps; g.w[0] = c->lm_head; g.rows[0] = d.vocab; g.total_rows = d.vocab;
         g.out = head->logits; g.out_stride = d.vocab; g.ncols = head->n_cols;
         if (mfma) {
@@ -579,6 +587,7 @@ int fill_recompute(d3_ctx* c, int pos_begin, int pos_end, hipStream_t s) {
         void* k_layer = c->k_cache + (size_t)l * c->kv_layer_bytes();
         void* v_layer = c->v_cache + (size_t)l * c->kv_layer_bytes();
         GemvArgs g{};
+        g.part = c->at<float>(c->lay.gemm_part); g.part_tickets = c->at<int>(c->lay.gemm_tickets);
         g.K = dm; g.eps = d.rms_eps; g.w[0] = w.wk; g.w[1] = w.wv; g.rows[0] = kvdim; g.rows[1] = kvdim; g.total_rows = 2 * kvdim;
         g.out = kv; g.out_stride = 2 * kvdim; g.ncols = B;
         if (mfma) {

@@ -9,6 +9,8 @@ namespace d3 {
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per forward pass
 constexpr int kMaxSplits = 32;     // context splits of one attention head
+constexpr size_t kGemmPartBytes = 16u << 20;   // partial accumulators of a K-sliced wide MFMA projection
+constexpr int kGemmPartTickets = 2048;         // row groups such a projection may have
 constexpr int kSsqStride = 512;    // partial sums of squares kept per column (one per workgroup of the producing projection)
 
 typedef uint16_t bf16_t;           // bf16 bit pattern
@@ -100,13 +102,18 @@ struct GemvArgs {
     int ssq_parts;
     float* ssq_out;          // [ncols][kSsqStride]
     const float* gain_next;  // [total_rows]
+    // wide MFMA kernel (17..32 columns), K cut into slices: partial accumulators and one arrival counter per row
+    // group (zero between launches)
+    float* part;
+    int* part_tickets;
     unsigned long long* debug_ts;   // optional: per-workgroup 100 MHz timestamps (entry, staged, done)
     int head_start;                 // pause (units of 512 clocks) between issuing the activation loads and the weight preload
 };
 
 // returns hipError_t as int
 int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, int n_wg, hipStream_t s);
-int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups = nullptr);   // n_groups: workgroups launched (= parts written to ssq_out)
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups = nullptr);
+int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups);   // 17..32 columns   // n_groups: workgroups launched (= parts written to ssq_out)
 size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
 
 // first step of a pass on the MFMA path: hi + lo = x * gain (bf16 halves), ssq[col * kSsqStride] = sum(x^2)

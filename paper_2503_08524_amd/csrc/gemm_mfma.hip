@@ -29,6 +29,11 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+#ifdef D3_EXP_NO_B
+constexpr bool kExpNoB = true;    // timing experiment only: activations are not re-read (results are wrong)
+#else
+constexpr bool kExpNoB = false;
+#endif
 constexpr int U = 4;            // k-steps (of 32) a wave takes per turn: 256 contiguous bytes of each row
 constexpr int kTileRowBytes = 272;   // LDS pitch of a staged 16 x 256 B tile (+16 B: conflict-free fragment reads)
 constexpr int kTileBytes = 16 * kTileRowBytes;
@@ -140,9 +145,9 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 tile_to_frags(gb[2 * t], tile, bf[2 * t]);
-                if (next) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+                if (next && !kExpNoB) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
                 tile_to_frags(gb[2 * t + 1], tile, bf[2 * t + 1]);
-                if (next) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+                if (next && !kExpNoB) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
             }
         }
 #pragma unroll
@@ -253,6 +258,12 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     }
 }
 
+// D3_MFMA_WIDE=0 keeps 17..32 columns on this file's kernel (for comparisons)
+bool wide_enabled() {
+    static const bool on = [] { const char* e = getenv("D3_MFMA_WIDE"); return !(e && e[0] == '0'); }();
+    return on;
+}
+
 int env_int(const char* name, int lo, int hi) {
     const char* e = getenv(name);
     if (!e) return 0;
@@ -286,6 +297,7 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
+    if (nt == 2 && a.part && wide_enabled()) return launch_gemm_mfma_wide(a, mode, n_cu, s, n_groups);
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
     const bool pack = a.ncols <= 8;

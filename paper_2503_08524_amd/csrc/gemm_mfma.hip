@@ -29,11 +29,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#ifdef D3_EXP_NO_B
-constexpr bool kExpNoB = true;    // timing experiment only: activations are not re-read (results are wrong)
-#else
-constexpr bool kExpNoB = false;
-#endif
 constexpr int U = 4;            // k-steps (of 32) a wave takes per turn: 256 contiguous bytes of each row
 constexpr int kTileRowBytes = 272;   // LDS pitch of a staged 16 x 256 B tile (+16 B: conflict-free fragment reads)
 constexpr int kTileBytes = 16 * kTileRowBytes;
@@ -145,9 +140,9 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
                 tile_to_frags(gb[2 * t], tile, bf[2 * t]);
-                if (next && !kExpNoB) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+                if (next) tile_load_cached(gb[2 * t], a.x_hi + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
                 tile_to_frags(gb[2 * t + 1], tile, bf[2 * t + 1]);
-                if (next && !kExpNoB) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
+                if (next) tile_load_cached(gb[2 * t + 1], a.x_lo + (size_t)(t * 16) * a.x_stride + k1, a.x_stride, k1, K);
             }
         }
 #pragma unroll

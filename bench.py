@@ -182,6 +182,12 @@ def main() -> int:
         keep1, _, _ = binding.d3_plan_depth(shape.L, 1.0, start, 0, G)
         kernel = "persistent decode step (all %d blocks + lm_head + argmax in one launch)" % shape.L
         kclass, bytes_per_launch = binding.D3_K_STEP, algorithmic_bytes(shape, B, P, G, keep1, kv_bytes) / (G - 1)
+    elif args.config == "7b-b32":
+        # at batch 32 the cache rows outweigh the weights: attention is the dominant kernel (one launch per block;
+        # bytes averaged over the request's steps: K and V rows of B sequences, read once)
+        kernel = "decode attention (RoPE + KV append + split merge included)"
+        kv_row = 2 * shape.H_kv * shape.hd * kv_bytes
+        kclass, bytes_per_launch = binding.D3_K_ATTN, sum(B * (P + i) * kv_row for i in range(1, G)) / (G - 1) + 2 * B * shape.d * 4
     else:
         kernel = "fused RMSNorm + gate/up + SiLU*mul projection"
         kclass, bytes_per_launch = binding.D3_K_GATE_UP, 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4

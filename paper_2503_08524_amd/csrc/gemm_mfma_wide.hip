@@ -220,17 +220,27 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
         if (!is_last) return;
 #pragma unroll
         for (int r = 0; r < NA; ++r) { acc[r][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-        for (int ks = 0; ks < KS; ++ks) {
-            const float* p = a.part + (((size_t)blockIdx.x * KS + ks) * W + wave) * (ACC * 64) + lane;
-            float v[ACC];
+        // four slices per round trip: all their loads are issued before the first is added (slice order is kept)
+        for (int ks0 = 0; ks0 < KS; ks0 += 4) {
+            float v[4][ACC];
 #pragma unroll
-            for (int j = 0; j < ACC; ++j) v[j] = ld_agent(p + j * 64);
+            for (int q = 0; q < 4; ++q) {
+                const int ks = ks0 + q < KS ? ks0 + q : KS - 1;
+                const float* p = a.part + (((size_t)blockIdx.x * KS + ks) * W + wave) * (ACC * 64) + lane;
 #pragma unroll
-            for (int r = 0; r < NA; ++r)
+                for (int j = 0; j < ACC; ++j) v[q][j] = ld_agent(p + j * 64);
+            }
 #pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
+            for (int q = 0; q < 4; ++q) {
+                if (ks0 + q < KS) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[r][tt][e] += v[(r * 2 + tt) * 4 + e];
+                    for (int r = 0; r < NA; ++r)
+#pragma unroll
+                        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[r][tt][e] += v[q][(r * 2 + tt) * 4 + e];
+                }
+            }
         }
     }
 

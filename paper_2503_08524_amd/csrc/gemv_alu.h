@@ -10,7 +10,10 @@
 
 namespace d3 {
 
-constexpr int kGemvWaves = 4;
+#ifndef D3_GEMV_WAVES
+#define D3_GEMV_WAVES 4
+#endif
+constexpr int kGemvWaves = D3_GEMV_WAVES;   // waves per workgroup (they share the staged activations)
 constexpr int kGemvThreads = kGemvWaves * kWave;
 constexpr int kGemvStageR = 12;             // float4 activation loads a thread issues ahead of the weights (K <= 12288 in one round)
 constexpr int kGemvLdsBudget = 60 * 1024;   // dynamic LDS per workgroup for the activations

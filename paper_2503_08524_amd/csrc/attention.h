@@ -65,12 +65,19 @@ struct AttnShared {
 // Second half of a split (all waves have put their running max, sum and unnormalised output of every head
 // into `sh` and passed a barrier): merge the waves, publish the split's partial of every head, and let the
 // split that arrives last at the (column, KV head) counter merge all splits and write the output.
-template <int HD, bool FUSED, int NW, int G>
+//
+// The G entries of `sh` are GH heads of each of G / GH consecutive columns: entry e is head h0 + e % GH of column
+// c + e / GH (decode: GH = G, one column; a prompt chunk's query tile: several columns).  Entries whose column
+// lies past the pass are dropped.
+template <int HD, bool FUSED, int NW, int G, int GH = G>
 __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split, int h0, int c, int n_live, AttnShared<HD, NW, G>& sh) {
     const int tid = threadIdx.x;
+    constexpr int RND = (G * HD > 4 * NW * 64) ? 2 : 8;   // splits fetched per round of the final merge (register budget)
     // ---- merge the waves; publish this split's partial of every head ----
     for (int idx = tid; idx < G * HD; idx += NW * 64) {
         const int g = idx / HD, t = idx % HD;
+        const int ce = c + g / GH, he = h0 + g % GH;
+        if (ce >= a.ncols) continue;
         float M = sh.m[g][0];
 #pragma unroll
         for (int w = 1; w < NW; ++w) M = fmaxf(M, sh.m[g][w]);
@@ -83,7 +90,7 @@ __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split,
         }
         if (n_live == 1) {                             // the only split of this column: the result is final
             const float r = o / L;
-            const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + g) * HD + t;
+            const size_t oi = (size_t)ce * a.H * HD + (size_t)he * HD + t;
             if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
             if (a.out_hi) {
                 const uint32_t hb = f32_to_bf16(r);
@@ -92,7 +99,7 @@ __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split,
             }
             continue;
         }
-        const size_t pidx = ((size_t)c * a.H + h0 + g) * a.n_splits + split;
+        const size_t pidx = ((size_t)ce * a.H + he) * a.n_splits + split;
         st_agent(&a.part_o[pidx * HD + t], o);
         if (t == 0) { st_agent(&a.part_ml[pidx * 2], M); st_agent(&a.part_ml[pidx * 2 + 1], L); }
     }
@@ -115,15 +122,17 @@ __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split,
     float gm[ITEMS], L[ITEMS], o[ITEMS];
 #pragma unroll
     for (int i = 0; i < ITEMS; ++i) { gm[i] = -INFINITY; L[i] = 0.f; o[i] = 0.f; }
-    for (int s0 = 0; s0 < n_live; s0 += 8) {
-        float ms[ITEMS][8], ls[ITEMS][8], os[ITEMS][8];
+    for (int s0 = 0; s0 < n_live; s0 += RND) {
+        float ms[ITEMS][RND], ls[ITEMS][RND], os[ITEMS][RND];
 #pragma unroll
         for (int i = 0; i < ITEMS; ++i) {
             int idx = tid + i * (NW * 64);
             idx = idx < G * HD ? idx : G * HD - 1;
-            const size_t p0 = ((size_t)c * a.H + h0 + idx / HD) * a.n_splits;
+            int ge = idx / HD;
+            if (c + ge / GH >= a.ncols) ge = 0;           // a dropped entry re-reads entry 0 (the result is not stored)
+            const size_t p0 = ((size_t)(c + ge / GH) * a.H + h0 + ge % GH) * a.n_splits;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < RND; ++k) {
                 const int sidx = s0 + k < n_live ? s0 + k : n_live - 1;
                 ms[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2]);
                 ls[i][k] = ld_agent(&a.part_ml[(p0 + sidx) * 2 + 1]);
@@ -134,11 +143,11 @@ __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split,
         for (int i = 0; i < ITEMS; ++i) {
             float rm = gm[i];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[i][k]);
+            for (int k = 0; k < RND; ++k) if (s0 + k < n_live) rm = fmaxf(rm, ms[i][k]);
             const float keep = exp2f(gm[i] - rm);         // -inf on the first round: exp2(-inf) = 0
             L[i] *= keep; o[i] *= keep;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < RND; ++k) {
                 if (s0 + k < n_live) {
                     const float w = exp2f(ms[i][k] - rm);
                     L[i] += ls[i][k] * w;
@@ -152,8 +161,10 @@ __device__ __forceinline__ void attn_merge_publish(const AttnArgs& a, int split,
     for (int i = 0; i < ITEMS; ++i) {
         const int idx = tid + i * (NW * 64);
         if (idx >= G * HD) continue;
+        const int ge = idx / HD, ce = c + ge / GH;
+        if (ce >= a.ncols) continue;
         const float r = o[i] / L[i];
-        const size_t oi = (size_t)c * a.H * HD + (size_t)(h0 + idx / HD) * HD + idx % HD;
+        const size_t oi = (size_t)ce * a.H * HD + (size_t)(h0 + ge % GH) * HD + idx % HD;
         if (FUSED) st_agent(&a.out[oi], r); else a.out[oi] = r;
         if (a.out_hi) {
             const uint32_t hb = f32_to_bf16(r);
@@ -594,6 +605,144 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
     if (g == 0 && i < G) { sh.merge.m[i][wave] = m; sh.merge.l[i][wave] = lsum; }
     __syncthreads();
     attn_merge_publish<128, false, NW, G>(a, split, h0, c, n_live, sh.merge);
+}
+
+// ---------------- prompt chunks: a tile of consecutive queries on the matrix cores ----------------
+// A prompt chunk holds consecutive positions of ONE sequence.  The kernel above, given a column at a time, would
+// read the whole context once per query; here the 16 entries of the matrix dimension are QT = 16 / GH consecutive
+// queries (columns c0 .. c0 + QT - 1) times the GH query heads of one KV head, so a cache row is read once per QT
+// queries.  Entry e = query e / GH, head h0 + e % GH; its context ends at its own position (causal mask per
+// entry).  The K/V rows of the chunk are already in the cache (rope_append_kernel ran before), q is rotated.
+template <int NW, int GH>
+__device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, int h0, int c0, AttnMfmaShared<NW, 16>& sh) {
+    constexpr int HD = 128;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int c_last = min(c0 + 16 / GH, a.ncols) - 1;               // last column of the tile that exists
+    const int seq = a.cm.seq(c0), ctx_max = a.cm.pos(c_last) + 1;
+    const int j0 = split * a.split_len;
+    const int j1 = min(j0 + a.split_len, ctx_max);
+    if (j0 >= j1) return;
+    const int n_live = (ctx_max + a.split_len - 1) / a.split_len;
+    const int kvh = h0 / (a.H / a.H_kv);
+    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
+    const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
+    const float scale = 1.4426950408889634f / sqrtf((float)HD);
+    const int ci = c0 + i / GH;                                      // this lane's entry: column, head, end of context
+    const bool live = ci < a.ncols;
+    const int ctx_i = live ? a.cm.pos(ci) + 1 : 0;
+
+    attn_half8 qhi[4], qlo[4];
+    {
+        const float* qp = a.q + (size_t)(live ? ci : c0) * a.q_stride + (size_t)(h0 + i % GH) * HD + 8 * g;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            const float4 t0 = *reinterpret_cast<const float4*>(qp + 32 * kk), t1 = *reinterpret_cast<const float4*>(qp + 32 * kk + 4);
+            const float qf[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = live ? qf[e] * scale : 0.f;
+                const f16_t h = (f16_t)v;
+                qhi[kk][e] = h;
+                qlo[kk][e] = (f16_t)(v - (float)h);
+            }
+        }
+    }
+
+    float m = -INFINITY, lsum = 0.f;
+    attn_f32x4 acc[8];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) acc[nt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+    char* kbuf = sh.stage.k[wave];
+    char* vbuf = sh.stage.v[wave];
+    float* keepbuf = sh.stage.keep[wave];
+    const int lrow = lane >> 4, lseg = lane & 15;
+
+    for (int r0 = j0 + wave * 32; r0 < j1; r0 += NW * 32) {
+        uint4 kreg[2][4], vreg[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            int row = r0 + 4 * q + lrow;
+            row = row < j1 ? row : j1 - 1;
+            kreg[q >> 2][q & 3] = *reinterpret_cast<const uint4*>(Kb + (size_t)row * HD + 8 * lseg);   // re-read by the next tiles: cached
+            vreg[q] = *reinterpret_cast<const uint4*>(Vb + (size_t)row * HD + 8 * lseg);
+        }
+        attn_f32x4 S[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<uint4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[t][q];
+            __builtin_amdgcn_wave_barrier();
+            S[t] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf + i * kAttnPitch + kk * 64 + g * 16);
+                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qhi[kk], S[t], 0, 0, 0);
+                S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qlo[kk], S[t], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = r0 + 16 * t + 4 * g + e;
+                if (row >= j1 || row >= ctx_i) S[t][e] = -INFINITY;  // past the split, or after this entry's own position
+                mx = fmaxf(mx, S[t][e]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m, mx);
+        const bool any = m_new > -INFINITY;                           // an entry may have no row yet (its context ends earlier)
+        const float keep = any ? exp2f(m - m_new) : 1.f;
+        attn_half8 phi, plo;
+        float ps = 0.f;
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p = any ? exp2f(S[t][e] - m_new) : 0.f;
+                ps += p;
+                const f16_t h = (f16_t)p;
+                phi[4 * t + e] = h;
+                plo[4 * t + e] = (f16_t)(p - (float)h);
+            }
+        lsum = lsum * keep + ps;
+        m = m_new;
+        if (g == 0) keepbuf[i] = keep;
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            *reinterpret_cast<uint4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
+        __builtin_amdgcn_wave_barrier();
+        const float4 kf = *reinterpret_cast<const float4*>(keepbuf + 4 * g);
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+            acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
+            attn_half8 vb;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int row = j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4);
+                vb[j] = *reinterpret_cast<const f16_t*>(vbuf + row * kAttnPitch + (16 * nt + i) * 2);
+            }
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    __syncthreads();
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) sh.merge.o[4 * g + e][wave][16 * nt + i] = acc[nt][e];
+    if (g == 0) { sh.merge.m[i][wave] = m; sh.merge.l[i][wave] = lsum; }
+    __syncthreads();
+    attn_merge_publish<128, false, NW, 16, GH>(a, split, h0, c0, n_live, sh.merge);
 }
 
 }  // namespace d3

@@ -28,6 +28,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
     attn_split_mfma<ROPE, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
 }
 
+// grid: (split, KV-head group, tile of 16 / GH consecutive queries)
+template <int GH>
+__global__ __launch_bounds__(256) void attn_qtile_kernel(AttnArgs a) {
+    __shared__ AttnMfmaShared<4, 16> sh;
+    attn_qtile_mfma<4, GH>(a, blockIdx.x, blockIdx.y * GH, blockIdx.z * (16 / GH), sh);
+}
+
 // D3_ATTN_MFMA=0 keeps grouped-query attention on the vector ALUs (for comparisons)
 bool attn_mfma_enabled() {
     static const bool on = [] { const char* e = getenv("D3_ATTN_MFMA"); return !(e && e[0] == '0'); }();
@@ -37,6 +44,17 @@ bool attn_mfma_enabled() {
 template <typename T, int HD, bool ROPE>
 int launch_g(const AttnArgs& a, hipStream_t s) {
     const int group = a.H / a.H_kv;
+    if constexpr (std::is_same<T, f16_t>::value && HD == 128 && !ROPE) {
+        if (a.qtile && (group == 1 || group == 2 || group == 4 || group == 8) && attn_mfma_enabled()) {
+            const int qt = 16 / group;
+            dim3 grid(a.n_splits, a.H / group, (a.ncols + qt - 1) / qt);
+            if (group == 8) hipLaunchKernelGGL((attn_qtile_kernel<8>), grid, dim3(256), 0, s, a);
+            else if (group == 4) hipLaunchKernelGGL((attn_qtile_kernel<4>), grid, dim3(256), 0, s, a);
+            else if (group == 2) hipLaunchKernelGGL((attn_qtile_kernel<2>), grid, dim3(256), 0, s, a);
+            else hipLaunchKernelGGL((attn_qtile_kernel<1>), grid, dim3(256), 0, s, a);
+            return (int)hipGetLastError();
+        }
+    }
     if constexpr (std::is_same<T, f16_t>::value && HD == 128) {
         if ((group == 4 || group == 8) && attn_mfma_enabled()) {
             dim3 grid(a.n_splits, a.H / group, a.ncols);

@@ -102,6 +102,7 @@ struct d3_ctx {
     Layout lay;
     int n_cu;
     int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
+    bool prefill_by_seq;          // prompt pass one sequence at a time (D3_PREFILL_BY_SEQ, default on)
     int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU, default 2)
     int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
@@ -180,6 +181,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->gemv_wgs_per_cu = 3;
     c->gemv_head_start = 0;
     c->attn_wgs_per_cu = 2;
+    c->prefill_by_seq = true;
+    if (const char* env = getenv("D3_PREFILL_BY_SEQ")) c->prefill_by_seq = atoi(env) != 0;
     if (const char* env = getenv("D3_ATTN_WGS_PER_CU")) { const int v = atoi(env); if (v >= 1 && v <= 16) c->attn_wgs_per_cu = v; }
     if (const char* env = getenv("D3_GEMV_HEAD_START")) { const int v = atoi(env); if (v >= 0 && v <= 64) c->gemv_head_start = v; }
     if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {
@@ -280,10 +283,12 @@ struct HeadOut {       // what to do after the last block
 };
 
 // Attention split geometry for a pass whose longest context is `ctx` rows.
-void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split_len, int* n_splits) {
-    // workgroups per split: one per (column, KV head) when the group size has a grouped kernel, else per query head
+void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split_len, int* n_splits, bool qtile = false) {
+    // workgroups per split: one per (column, KV head) when the group size has a grouped kernel, else per query head;
+    // a prompt chunk on the query-tile kernel: one per (tile of 16 / group queries, KV head)
     const int group = c->desc.n_heads / c->desc.n_kv_heads;
-    const int heads = ncols * ((group == 2 || group == 4 || group == 8) ? c->desc.n_kv_heads : c->desc.n_heads);
+    int heads = ncols * ((group == 2 || group == 4 || group == 8) ? c->desc.n_kv_heads : c->desc.n_heads);
+    if (qtile) heads = ((ncols * group + 15) / 16) * c->desc.n_kv_heads;
     int want = (target_wgs + heads - 1) / heads;
     if (want < 1) want = 1;
     if (want > kMaxSplits) want = kMaxSplits;
@@ -317,7 +322,8 @@ int alu_projection(d3_ctx* c, GemvArgs g, int first, int count, int mode, bool n
 // save_before >= 0: the residual that enters the first listed block >= save_before (the one after the last, if none)
 // is copied to the workspace's h_skip: it is what the blocks of the drop window would have seen.
 int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_t* ids, int n_ids,
-            float* hidden_dump, int dump_first, int dump_cols, const HeadOut* head, hipStream_t s, int save_before = -1) {
+            float* hidden_dump, int dump_first, int dump_cols, const HeadOut* head, hipStream_t s, int save_before = -1,
+            int dump_total = -1, int dump_dst = 0) {
     const d3_model_desc& d = c->desc;
     const int dm = d.d_model, hd = d.head_dim, qdim = d.n_heads * hd, kvdim = d.n_kv_heads * hd, qkv_dim = qdim + 2 * kvdim, F = d.d_ffn;
     float* x = c->at<float>(c->lay.x);
@@ -339,15 +345,20 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, s));
     auto dump = [&](int slot) -> int {
         if (!hidden_dump) return 0;
-        return (int)hipMemcpyAsync(hidden_dump + (size_t)slot * dump_cols * dm, x + (size_t)dump_first * dm,
+        // destination slot layout [dump_total columns][d]; this pass fills columns dump_dst .. dump_dst + dump_cols - 1
+        return (int)hipMemcpyAsync(hidden_dump + ((size_t)slot * (dump_total < 0 ? dump_cols : dump_total) + dump_dst) * dm, x + (size_t)dump_first * dm,
                                    (size_t)dump_cols * dm * sizeof(float), hipMemcpyDeviceToDevice, s);
     };
     D3_HIP(dump(0));
 
     auto alu = [&](GemvArgs g, int first, int count, int mode, bool norm) -> int { return alu_projection(c, g, first, count, mode, norm, s); };
 
+    // a prompt chunk of one sequence (consecutive positions): tiles of queries share the cache rows they read
+    const int grp = d.n_heads / d.n_kv_heads;
+    const bool qtile = c->prefill_by_seq && mfma && cm.B == 1 && ncols >= 2 && d.kv_dtype == D3_F16 && hd == 128 &&
+                       (grp == 1 || grp == 2 || grp == 4 || grp == 8);
     int split_len, n_splits;
-    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, c->attn_wgs_per_cu * c->n_cu, &split_len, &n_splits);
+    pick_splits(c, ncols, cm.pos(ncols - 1) + 1, c->attn_wgs_per_cu * c->n_cu, &split_len, &n_splits, qtile);
 
     // Matrix-core path: RMSNorm lives inside the projections.  Whoever writes the residual also writes the split of
     // residual * (gain of the norm that reads it next) and partial sums of squares; the reading projection scales its
@@ -402,6 +413,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         at.part_o = c->at<float>(c->lay.part_o); at.part_ml = c->at<float>(c->lay.part_ml); at.tickets = c->at<int>(c->lay.tickets);
         at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
         at.rope_cs = rope_in_attn ? rope_cs : nullptr;
+        at.qtile = qtile ? 1 : 0;
         {
             Timed t(c, D3_K_ATTN, s);
             D3_HIP(launch_attention(at, d.kv_dtype, s));
@@ -509,19 +521,37 @@ extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t
 
     std::vector<int32_t> all(d.n_layers);
     for (int l = 0; l < d.n_layers; ++l) all[l] = l;
-    const int chunk = (kMaxCols / B) * B;
-    const int total = B * P;
-    // position-major columns in chunks that are multiples of B: the last B columns of the last
-    // chunk are the last prompt position of every sequence
-    for (int base = 0; base < total;) {
-        const int ncols = total - base < chunk ? total - base : chunk;
-        const bool last = base + ncols == total;
-        ColMap cm{base, B, P, pos_begin};
-        HeadOut head{ncols - B, B, logits ? logits : ctx->at<float>(ctx->lay.logits), next_tok};
-        int rc = forward(ctx, tokens, cm, ncols, all.data(), d.n_layers, last ? hidden_dump : nullptr, ncols - B, B,
-                         last ? &head : nullptr, s);
-        if (rc != D3_OK) return rc;
-        base += ncols;
+    float* lg = logits ? logits : ctx->at<float>(ctx->lay.logits);
+    if (ctx->prefill_by_seq) {
+        // one sequence at a time, 32 consecutive positions per pass: the attention of such a chunk reads every cache
+        // row once per tile of queries instead of once per query
+        for (int b = 0; b < B; ++b) {
+            for (int base = 0; base < P;) {
+                const int ncols = P - base < kMaxCols ? P - base : kMaxCols;
+                const bool last = base + ncols == P;
+                ColMap cm{base, 1, P, pos_begin, b};
+                HeadOut head{ncols - 1, 1, lg + (size_t)b * d.vocab, next_tok + b};
+                int rc = forward(ctx, tokens, cm, ncols, all.data(), d.n_layers, last ? hidden_dump : nullptr, ncols - 1, 1,
+                                 last ? &head : nullptr, s, -1, B, b);
+                if (rc != D3_OK) return rc;
+                base += ncols;
+            }
+        }
+    } else {
+        const int chunk = (kMaxCols / B) * B;
+        const int total = B * P;
+        // position-major columns in chunks that are multiples of B: the last B columns of the last
+        // chunk are the last prompt position of every sequence
+        for (int base = 0; base < total;) {
+            const int ncols = total - base < chunk ? total - base : chunk;
+            const bool last = base + ncols == total;
+            ColMap cm{base, B, P, pos_begin};
+            HeadOut head{ncols - B, B, lg, next_tok};
+            int rc = forward(ctx, tokens, cm, ncols, all.data(), d.n_layers, last ? hidden_dump : nullptr, ncols - B, B,
+                             last ? &head : nullptr, s);
+            if (rc != D3_OK) return rc;
+            base += ncols;
+        }
     }
     for (int p = pos_begin; p < pos_begin + P; ++p) { ctx->row_drop_begin[p] = 0; ctx->row_n_drop[p] = 0; }
     ctx->prefilled = true;

@@ -25,7 +25,8 @@ inline int kv_elem_bytes(int kv_dtype) { return kv_dtype == 0 ? 4 : 2; }
 // enumeration of the [B][P] prompt, so the last B columns are the last positions.
 struct ColMap {
     int base, B, P, pos_begin;
-    __host__ __device__ int seq(int c) const { return (base + c) % B; }
+    int seq0 = 0;          // first sequence of the pass (a prompt chunk of one sequence: B = 1, seq0 = that sequence)
+    __host__ __device__ int seq(int c) const { return seq0 + (base + c) % B; }
     __host__ __device__ int pos(int c) const { return pos_begin + (base + c) / B; }
     __host__ __device__ int tok_index(int c) const { return seq(c) * P + (base + c) / B; }
 };
@@ -138,6 +139,7 @@ int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s);
 struct AttnArgs {
     const float* q;        // [ncols][q_stride]: q heads, then (rope_cs set) the newest k and v rows; rotated unless rope_cs is set
     const float2* rope_cs; // optional [ncols][hd/2] (cos, sin): rotate q and k here and append the newest K/V row
+    int qtile;             // the columns are consecutive positions of one sequence (a prompt chunk): tiles of queries share the cache rows
     int q_stride;
     const void* k_cache;   // this block's cache
     const void* v_cache;

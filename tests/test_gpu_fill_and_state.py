@@ -249,3 +249,30 @@ def test_recompute_fill_call_rules():
     dec.fill_missing_kv(6, 7, binding.D3_FILL_COPY)                                     # COPY stays available for any row
     dec.sync_check()
     dec.close()
+
+
+def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split():
+    """A second prompt that starts at row 61: its chunk's query tiles (4 queries x 4 heads of a KV head at this shape) are
+    not aligned with the 64-row context splits, so some queries of a tile have no row in the last split while others do."""
+    shape = ModelShape("small-gqa", L=3, d=512, H=8, H_kv=2, hd=128, F=1376, V=2000, dtype="bf16")
+    B, P, G, alpha, start = 2, 50, 12, 0.9, 1
+    P2, G2 = 10, 3
+    w = d3_inputs.make_weights(shape, 3)
+    prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)
+    prompts2 = d3_inputs.make_prompt(B, P2, shape.V, seed=5)
+    forced2 = d3_inputs.make_prompt(B, G2 - 1, shape.V, seed=6)
+    max_seq = P + G + P2 + G2
+    print("case continuation across a split boundary", flush=True)
+    gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq, fill_each_step=True)
+    dec = gpu["decoder"]
+    n_rows = P + G - 1
+    assert n_rows == 61
+    gpu2 = helpers.gpu_generate(shape, w, prompts2, G2, alpha, start, forced=forced2, decoder=dec, pos_begin=n_rows)
+    model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq)
+    gens2 = []
+    for b, gen in enumerate(gens):
+        oracle.fill_generated_rows(gen, P, G)
+        gens2.append(oracle.generate(model, prompts2[b], G2, alpha, start, seq=gen.seq, pos_begin=n_rows, forced=forced2[b]))
+    wl, wh = helpers.compare(gpu2, gens2, G2)
+    print(f"  worst logit abs err {wl:.3e}, hidden {wh:.3e}", flush=True)

@@ -57,7 +57,7 @@ int check_desc(const d3_model_desc* d) {
 }
 
 Layout make_layout(const d3_model_desc& d) {
-    const size_t C = kMaxCols, qdim = (size_t)d.n_heads * d.head_dim;
+    const size_t C = kPassCols, qdim = (size_t)d.n_heads * d.head_dim;
     const size_t qkv_dim = (size_t)(d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
     const size_t s_dim = qdim > (size_t)d.d_model ? qdim : (size_t)d.d_model;
     Layout l{};
@@ -227,7 +227,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     std::vector<double> inv(desc->head_dim / 2);
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kMaxCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
+    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kPassCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.gemm_tickets), 0, (size_t)kGemmPartTickets * sizeof(int));
     if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
@@ -525,9 +525,11 @@ extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t
     if (ctx->prefill_by_seq) {
         // one sequence at a time, 32 consecutive positions per pass: the attention of such a chunk reads every cache
         // row once per tile of queries instead of once per query
+        // the matrix-core path takes 64 columns a pass (the weights are streamed once per pass)
+        const int chunk_cols = ctx->mfma_ok && gemm_mfma_wide_enabled() ? kPassCols : kMaxCols;
         for (int b = 0; b < B; ++b) {
             for (int base = 0; base < P;) {
-                const int ncols = P - base < kMaxCols ? P - base : kMaxCols;
+                const int ncols = P - base < chunk_cols ? P - base : chunk_cols;
                 const bool last = base + ncols == P;
                 ColMap cm{base, 1, P, pos_begin, b};
                 HeadOut head{ncols - 1, 1, lg + (size_t)b * d.vocab, next_tok + b};

@@ -7,7 +7,8 @@
 namespace d3 {
 
 constexpr int kWave = 64;          // CDNA wavefront
-constexpr int kMaxCols = 32;       // columns (sequence, position pairs) per forward pass
+constexpr int kMaxCols = 32;       // largest batch; columns of a decode pass
+constexpr int kPassCols = 64;      // columns of a prompt chunk on the matrix-core path (workspace buffers hold this many)
 constexpr int kMaxSplits = 32;     // context splits of one attention head
 constexpr size_t kGemmPartBytes = 16u << 20;   // partial accumulators of a K-sliced wide MFMA projection
 constexpr int kGemmPartTickets = 2048;         // row groups such a projection may have
@@ -114,7 +115,8 @@ struct GemvArgs {
 // returns hipError_t as int
 int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, int n_wg, hipStream_t s);
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups = nullptr);
-int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups);   // 17..32 columns   // n_groups: workgroups launched (= parts written to ssq_out)
+int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups);   // 17..kPassCols columns
+bool gemm_mfma_wide_enabled();   // false: D3_MFMA_WIDE=0, passes are limited to kMaxCols columns   // n_groups: workgroups launched (= parts written to ssq_out)
 size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
 
 // first step of a pass on the MFMA path: hi + lo = x * gain (bf16 halves), ssq[col * kSsqStride] = sum(x^2)

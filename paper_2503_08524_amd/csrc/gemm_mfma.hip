@@ -253,12 +253,6 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     }
 }
 
-// D3_MFMA_WIDE=0 keeps 17..32 columns on this file's kernel (for comparisons)
-bool wide_enabled() {
-    static const bool on = [] { const char* e = getenv("D3_MFMA_WIDE"); return !(e && e[0] == '0'); }();
-    return on;
-}
-
 int env_int(const char* name, int lo, int hi) {
     const char* e = getenv(name);
     if (!e) return 0;
@@ -285,6 +279,12 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 
 }  // namespace
 
+// D3_MFMA_WIDE=0 keeps 17..32 columns on this file's kernel (for comparisons) and limits a pass to 32 columns
+bool gemm_mfma_wide_enabled() {
+    static const bool on = [] { const char* e = getenv("D3_MFMA_WIDE"); return !(e && e[0] == '0'); }();
+    return on;
+}
+
 // Requirements (checked by the caller): bf16 weights; K % 32 == 0; total_rows and every rows[m]
 // multiples of 16; 1 <= ncols <= 32; x_hi/x_lo hold 32 rows of x_stride elements (rows beyond
 // ncols may hold anything finite or not: their columns are never written); with ssq_out, total_rows / 16 <=
@@ -292,7 +292,8 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
-    if (nt == 2 && a.part && wide_enabled()) return launch_gemm_mfma_wide(a, mode, n_cu, s, n_groups);
+    if (nt == 2 && a.part && gemm_mfma_wide_enabled()) return launch_gemm_mfma_wide(a, mode, n_cu, s, n_groups);
+    if (a.ncols > kMaxCols) return (int)hipErrorInvalidValue;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
     const bool pack = a.ncols <= 8;

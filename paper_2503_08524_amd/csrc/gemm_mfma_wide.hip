@@ -1,5 +1,5 @@
-// Skinny GEMM on the matrix cores for 17..32 activation columns (large decode batches, the chunked
-// prompt pass): out[col][row] = sum_k W[row][k] * x[col][k], bf16 weights, activations x = hi + lo.
+// Skinny GEMM on the matrix cores for 17..64 activation columns (large decode batches: up to 32; the chunked
+// prompt pass: up to 64): out[col][row] = sum_k W[row][k] * x[col][k], bf16 weights, activations x = hi + lo.
 //
 // With 32 columns the activations of one 128-k turn are four 16 x 128 tiles (hi and lo of two column
 // tiles), twice the bytes of a weight tile pair: a kernel whose waves each fetch and re-shape their own
@@ -28,9 +28,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int U = 4;                 // k-steps (of 32) per turn
 constexpr int kPitch = 272;          // LDS pitch of a staged 16 x 256 B tile (+16 B: conflict-free fragment reads)
 constexpr int kTile = 16 * kPitch;
-constexpr int W = 4;                 // waves per workgroup
-constexpr int NB = 4;                // panel tiles: hi, lo of column tile 0, hi, lo of column tile 1
-constexpr int kPanel = NB * kTile;
 
 struct TileRegs { u32x4 q[4]; };
 
@@ -53,16 +50,20 @@ __device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32
     __builtin_amdgcn_wave_barrier();
 }
 
-// grid: (row groups of W * RT tiles, K slices)
-template <int MODE, int RT>
+// grid: (row groups of W * RT tiles, K slices).  CT column tiles (2: up to 32 columns, 4 waves per workgroup; 4: up to
+// 64 columns, 8 waves per workgroup, so that the bigger panel is shared by more row tiles).
+template <int MODE, int RT, int CT, int W>
 __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
     constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;
     constexpr int NA = RT * SW;                        // A tiles per wave and turn
+    constexpr int NB = 2 * CT;                         // panel tiles: hi, lo of every column tile
+    constexpr int kPanel = NB * kTile;
     constexpr int PBT = NB * 256 / (W * 64);           // 16-byte panel pieces per thread and turn (= 4)
-    __shared__ __attribute__((aligned(16))) char panel[2][kPanel];
-    __shared__ __attribute__((aligned(16))) char stage[W][kTile];
-    __shared__ float inv_rms[kMaxCols];
-    __shared__ float ssq_w[W][kMaxCols];
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][kPanel] panels, then [W][kTile] staging tiles
+    char (*panel)[kPanel] = reinterpret_cast<char (*)[kPanel]>(lds);
+    char (*stage)[kTile] = reinterpret_cast<char (*)[kTile]>(lds + 2 * kPanel);
+    __shared__ float inv_rms[kPassCols];
+    __shared__ float ssq_w[W][kPassCols];
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K, nks = K / 32, turns = (nks + U - 1) / U;
@@ -98,9 +99,11 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
         pdst[i] = tb * kTile + r * kPitch + pseg * 16;
     }
 
-    f32x4 acc[NA][2];
+    f32x4 acc[NA][CT];
 #pragma unroll
-    for (int r = 0; r < NA; ++r) { acc[r][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int r = 0; r < NA; ++r)
+#pragma unroll
+        for (int tt = 0; tt < CT; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     u32x4 pb[PBT];
     TileRegs ga[2][NA];                                // weight tiles of two turns in flight
@@ -135,7 +138,7 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
                 if (t * U + u < nks) {
                     const bf16x8 wa = __builtin_bit_cast(bf16x8, af[u]);
 #pragma unroll
-                    for (int tt = 0; tt < 2; ++tt) {
+                    for (int tt = 0; tt < CT; ++tt) {
                         const u32x4 bh = *reinterpret_cast<const u32x4*>(pan + (2 * tt) * kTile + (lane & 15) * kPitch + u * 64 + (lane >> 4) * 16);
                         const u32x4 bl = *reinterpret_cast<const u32x4*>(pan + (2 * tt + 1) * kTile + (lane & 15) * kPitch + u * 64 + (lane >> 4) * 16);
                         acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bh), acc[r][tt], 0, 0, 0);
@@ -199,15 +202,15 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
     }
 
     // ---- K slices: publish, count arrivals, the last one adds the slices up in order ----
-    constexpr int ACC = NA * 2 * 4;
+    constexpr int ACC = NA * CT * 4;
     if (KS > 1) {
         float* mine = a.part + (((size_t)blockIdx.x * KS + blockIdx.y) * W + wave) * (ACC * 64) + lane;
 #pragma unroll
         for (int r = 0; r < NA; ++r)
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
+            for (int tt = 0; tt < CT; ++tt)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) st_agent(mine + ((r * 2 + tt) * 4 + e) * 64, acc[r][tt][e]);
+                for (int e = 0; e < 4; ++e) st_agent(mine + ((r * CT + tt) * 4 + e) * 64, acc[r][tt][e]);
         wait_stores();                                 // this slice's partials have reached the coherence point
         __syncthreads();
         if (tid == 0) {
@@ -219,26 +222,29 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
         __syncthreads();
         if (!is_last) return;
 #pragma unroll
-        for (int r = 0; r < NA; ++r) { acc[r][0] = f32x4{0.f, 0.f, 0.f, 0.f}; acc[r][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-        // four slices per round trip: all their loads are issued before the first is added (slice order is kept)
-        for (int ks0 = 0; ks0 < KS; ks0 += 4) {
-            float v[4][ACC];
+        for (int r = 0; r < NA; ++r)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int tt = 0; tt < CT; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        // a few slices per round trip: all their loads are issued before the first is added (slice order is kept)
+        constexpr int RND = ACC > 16 ? 2 : 4;          // slices per round trip (register budget)
+        for (int ks0 = 0; ks0 < KS; ks0 += RND) {
+            float v[RND][ACC];
+#pragma unroll
+            for (int q = 0; q < RND; ++q) {
                 const int ks = ks0 + q < KS ? ks0 + q : KS - 1;
                 const float* p = a.part + (((size_t)blockIdx.x * KS + ks) * W + wave) * (ACC * 64) + lane;
 #pragma unroll
                 for (int j = 0; j < ACC; ++j) v[q][j] = ld_agent(p + j * 64);
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < RND; ++q) {
                 if (ks0 + q < KS) {
 #pragma unroll
                     for (int r = 0; r < NA; ++r)
 #pragma unroll
-                        for (int tt = 0; tt < 2; ++tt)
+                        for (int tt = 0; tt < CT; ++tt)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[r][tt][e] += v[q][(r * 2 + tt) * 4 + e];
+                            for (int e = 0; e < 4; ++e) acc[r][tt][e] += v[q][(r * CT + tt) * 4 + e];
                 }
             }
         }
@@ -246,12 +252,14 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
 
     // ---- epilogue from the accumulators: lane (i, g) holds column i of a column tile, rows 4g..4g+3 of each tile ----
     const int ci = lane & 15, g4 = lane >> 4;
-    float sq[2] = {0.f, 0.f};                          // this lane's share of sum(x_new^2) of columns ci, 16 + ci
+    float sq[CT];                                      // this lane's share of sum(x_new^2) of columns ci, 16 + ci, ...
+#pragma unroll
+    for (int tt = 0; tt < CT; ++tt) sq[tt] = 0.f;
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
         if (tile0 + r >= tiles) continue;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
+        for (int tt = 0; tt < CT; ++tt) {
             const int col = tt * 16 + ci;
             if (col >= a.ncols) continue;
             const int row = (tile0 + r) * 16 + 4 * g4;
@@ -293,7 +301,7 @@ __global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
     }
     if (MODE == MODE_RESID && a.ssq_out) {             // rows of a column: the 4 lane groups by butterfly, then the waves in order
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
+        for (int tt = 0; tt < CT; ++tt) {
             sq[tt] += __shfl_xor(sq[tt], 16, 64);
             sq[tt] += __shfl_xor(sq[tt], 32, 64);
             if (g4 == 0) ssq_w[wave][tt * 16 + ci] = sq[tt];
@@ -315,20 +323,31 @@ int env_int(const char* name, int lo, int hi) {
     return v >= lo && v <= hi ? v : 0;
 }
 
+template <int MODE, int RT, int CT, int W>
+int launch_one(const GemvArgs& a, int groups, int ks, hipStream_t s) {
+    constexpr size_t lds = (size_t)(2 * 2 * CT + W) * kTile;
+    auto* k = gemm_wide_kernel<MODE, RT, CT, W>;
+    if (lds > 48 * 1024) {
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (once != hipSuccess) return (int)once;
+    }
+    hipLaunchKernelGGL(k, dim3(groups, ks), dim3(W * 64), lds, s, a);
+    return (int)hipGetLastError();
+}
+
 template <int MODE>
-int launch_rt(const GemvArgs& a, int rt, int groups, int ks, hipStream_t s) {
+int launch_rt(const GemvArgs& a, int ct, int rt, int groups, int ks, hipStream_t s) {
+    if (ct == 4) return launch_one<MODE, 1, 4, 8>(a, groups, ks, s);
     if (rt == 2) {
         if constexpr (MODE == MODE_SWIGLU) return (int)hipErrorInvalidValue;
-        else hipLaunchKernelGGL((gemm_wide_kernel<MODE, 2>), dim3(groups, ks), dim3(W * 64), 0, s, a);
-    } else {
-        hipLaunchKernelGGL((gemm_wide_kernel<MODE, 1>), dim3(groups, ks), dim3(W * 64), 0, s, a);
+        else return launch_one<MODE, 2, 2, 4>(a, groups, ks, s);
     }
-    return (int)hipGetLastError();
+    return launch_one<MODE, 1, 2, 4>(a, groups, ks, s);
 }
 
 }  // namespace
 
-// Requirements: those of launch_gemm_mfma, 17 <= ncols <= 32; a.part holds kGemmPartBytes and a.part_tickets
+// Requirements: those of launch_gemm_mfma, 17 <= ncols <= kPassCols (x_hi / x_lo hold kPassCols rows); a.part holds kGemmPartBytes and a.part_tickets
 // kGemmPartTickets zeroed counters (the kernel leaves them zero).
 int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
@@ -337,21 +356,24 @@ int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, 
     // Measured at the 7B shape with 32 columns: one tile (pair) per wave beats two, and the launch is fastest when
     // its workgroups number about three per CU (what fits at once): K slices make up for the few row groups,
     // at least four turns each and at most eight of them (the publish / arrive / merge of the slices is not free).
+    const int ct = a.ncols > 32 ? 4 : 2;               // column tiles
+    const int w = ct == 4 ? 8 : 4;                     // waves per workgroup
     int rt = 1;
-    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (v == 1 || mode != MODE_SWIGLU) rt = v;
-    int groups = (tiles + W * rt - 1) / (W * rt);
-    int ks = 3 * n_cu / groups;
+    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (ct == 2 && (v == 1 || mode != MODE_SWIGLU)) rt = v;
+    int groups = (tiles + w * rt - 1) / (w * rt);
+    // up to 32 columns: three workgroups fit a CU; up to 64: one (its panels fill most of the LDS)
+    int ks = (ct == 4 ? 2 : 3) * n_cu / groups;
     if (ks > 8) ks = 8;
     if (const int v = env_int("D3_WIDE_KS", 1, 64)) ks = v;
     if (ks > turns / 4) ks = turns / 4;
     if (ks < 1) ks = 1;
-    while (ks > 1 && (size_t)groups * ks * W * (rt * sw * 2 * 4) * 64 * sizeof(float) > kGemmPartBytes) --ks;
+    while (ks > 1 && (size_t)groups * ks * w * (rt * sw * ct * 4) * 64 * sizeof(float) > kGemmPartBytes) --ks;
     if (groups > kGemmPartTickets) return (int)hipErrorInvalidValue;
     if (a.ssq_out && groups > kSsqStride) return (int)hipErrorInvalidValue;
     if (n_groups) *n_groups = groups;
-    if (mode == MODE_STORE) return launch_rt<MODE_STORE>(a, rt, groups, ks, s);
-    if (mode == MODE_RESID) return launch_rt<MODE_RESID>(a, rt, groups, ks, s);
-    return launch_rt<MODE_SWIGLU>(a, rt, groups, ks, s);
+    if (mode == MODE_STORE) return launch_rt<MODE_STORE>(a, ct, rt, groups, ks, s);
+    if (mode == MODE_RESID) return launch_rt<MODE_RESID>(a, ct, rt, groups, ks, s);
+    return launch_rt<MODE_SWIGLU>(a, ct, rt, groups, ks, s);
 }
 
 }  // namespace d3

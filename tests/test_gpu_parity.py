@@ -54,6 +54,15 @@ def test_small_bf16_matrix_core_path(B, P):
     _run(SMALL_BF16, B, P, 8, 0.9, 2, forced_seed=7)
 
 
+@pytest.mark.parametrize("shape,B,P", [(SMALL_BF16, 2, 24), (SMALL_BF16, 2, 97), (SMALL_BF16, 1, 81), (SMALL_GQA, 1, 80),
+                                       (SMALL_GQA, 2, 72), (SMALL_GQA, 1, 128)])
+def test_prompt_lengths_that_end_in_every_chunk_width(shape, B, P):
+    # the prompt pass takes one sequence at a time in chunks of 64 columns; the last chunk has 24, 33, 17, 16, 8 or 64
+    # columns here, which ends in each of the projection kernels (packed, 16-column, 32-column and 64-column) and in both
+    # attention paths of a prompt chunk (per column on the vector ALUs at head_dim 64, query tiles on the matrix cores at 128)
+    _run(shape, B, P, 4, 0.8, 1, forced_seed=9)
+
+
 @pytest.mark.parametrize("B,kv", [(1, "f16"), (3, "f16"), (2, "bf16"), (2, "f32")])
 def test_small_gqa(B, kv):
     _run(SMALL_GQA, B, 37, 6, 0.8, 1, forced_seed=8, kv_dtype=kv)

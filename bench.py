@@ -65,15 +65,19 @@ def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy"):
     return total
 
 
-def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy"):
-    """`requests` whole generation phases back to back; returns seconds (host clock around a device sync)."""
+def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy", table=None):
+    """`requests` whole generation phases back to back; returns seconds (host clock around a device sync).
+    table: (keep, drop_begin) of a schedule to follow instead of the power law."""
     cur = first_tok.clone()
     nxt = torch.zeros_like(cur)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(requests):
         dec.truncate(P)
-        dec.set_plan(alpha, start, 0, G)
+        if table is not None:
+            dec.set_plan_table(table[0], table[1])
+        else:
+            dec.set_plan(alpha, start, 0, G)
         cur.copy_(first_tok)
         for i in range(1, G):
             dec.decode_step(cur, i, nxt)
@@ -119,6 +123,9 @@ def main() -> int:
     ap.add_argument("--no-fill", action="store_true", help="same as --fill none")
     ap.add_argument("--fill", default="copy", choices=["copy", "recompute", "none"],
                     help="missing-state fill after every decode step (Section 3.2): KV copy (default), KV recompute, or none")
+    ap.add_argument("--compare-schedules", action="store_true",
+                    help="also time the comparison schedules of Section 4.1 at the headline alpha's average depth: the same "
+                         "power law with deep blocks dropped first, and linear decay with shallow blocks dropped first")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -175,6 +182,28 @@ def main() -> int:
             r["ideal_layer_count_ratio"] = shape.L / r["avg_blocks"]
             r["ideal_byte_ratio"] = results[1.0]["algorithmic_GB_per_token_step"] / r["algorithmic_GB_per_token_step"]
 
+    schedules = None
+    if args.compare_schedules and 1.0 in results:
+        # Same kernels, other plans (Section 4.1's comparison methods as far as the paper defines them: which blocks go
+        # first, and linear instead of power-law decay between bounds chosen to give at least the same average depth).
+        L = shape.L
+        d3_keep, d3_drop, _ = binding.d3_plan_depth(L, alphas[0], start, 0, G)
+        avg = float(d3_keep[1:G].mean())
+        last = max(0, min(L, int(2 * avg - L)))
+        while last < L and float(binding.d3_plan_depth_linear(L, L, last, 0, G)[0][1:G].mean()) < avg:
+            last += 1
+        plans = {"power law, middle blocks first (D^3)": (d3_keep, d3_drop),
+                 "power law, deep blocks first (early exit)": binding.d3_plan_depth(L, alphas[0], L - 1, 0, G)[:2],
+                 "linear %d -> %d, shallow blocks first" % (L, last): binding.d3_plan_depth_linear(L, L, last, 0, G)[:2]}
+        schedules = {}
+        for name, table in plans.items():
+            run_decode(dec, torch, first_tok, P, G, 1.0, start, args.warmup, fill, table=table)
+            secs = run_decode(dec, torch, first_tok, P, G, 1.0, start, args.steps, fill, table=table)
+            k = table[0]
+            schedules[name] = {"avg_blocks": float(k[1:G].mean()), "tokens_per_s": args.steps * (G - 1) * B / secs,
+                               "speedup_vs_full_depth": args.steps * (G - 1) * B / secs / results[1.0]["tokens_per_s"],
+                               "ideal_layer_count_ratio": L / float(k[1:G].mean())}
+
     # dominant kernel, every launch bracketed by HIP events on the launch stream, over one more full-depth request
     wbytes = 4 if shape.dtype == "f32" else 2
     if dec.persistent_workgroups > 0:
@@ -224,6 +253,8 @@ def main() -> int:
         "by_alpha": {str(a): r for a, r in results.items()},
         "roofline": roofline,
     }
+    if schedules is not None:
+        out["schedules"] = schedules
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, head["avg_blocks"])
     print(json.dumps(out))

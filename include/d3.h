@@ -82,6 +82,29 @@ const char *d3_last_error(void);
 int d3_plan_depth(int32_t L, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps,
                   int32_t *keep, int32_t *drop_begin, int32_t *layer_ids);
 
+/* Linear decay between two bounds, the schedule of the batched comparison
+ * method that Section 3.4 contrasts with the power law (Section 4.1 runs it
+ * "within upper and lower bounds of the executable layers"; its constants are
+ * not in the paper, so the bounds are arguments).  In integers, for i in
+ * [0, n_steps):  keep[i] = keep_first - ceil((keep_first - keep_last) * i /
+ * max(1, n_steps - 1)), i.e. floor of the straight line from keep_first at
+ * i = 0 to keep_last at the last step.  The dropped window follows the rule of
+ * d3_plan_depth, so start_layer = 0 drops shallow blocks first and start_layer
+ * = L - 1 deep blocks first (the two skip directions of Section 1 / Figure 1);
+ * anything between is the middle-first order of D^3.  Same outputs and
+ * ownership as d3_plan_depth.  D3_EINVAL unless L >= 1, 0 <= keep_last <=
+ * keep_first <= L, 0 <= start_layer < L, n_steps >= 0. */
+int d3_plan_depth_linear(int32_t L, int32_t keep_first, int32_t keep_last, int32_t start_layer,
+                         int32_t n_steps, int32_t *keep, int32_t *drop_begin, int32_t *layer_ids);
+
+/* Executed-block lists of a caller-made schedule (same table rule, Table 6):
+ * host int32 keep[n_steps], drop_begin[n_steps] in, layer_ids[n_steps*L] out
+ * (may be NULL: validation only).  D3_EINVAL unless every step has
+ * 0 <= keep[i] <= L and its window [drop_begin[i], drop_begin[i] + L - keep[i])
+ * inside [0, L). */
+int d3_plan_from_table(int32_t L, int32_t n_steps, const int32_t *keep, const int32_t *drop_begin,
+                       int32_t *layer_ids);
+
 /* Bytes of device workspace d3_create needs for this model (0 on a bad desc). */
 size_t d3_workspace_size(const d3_model_desc *desc);
 
@@ -99,6 +122,11 @@ int d3_destroy(d3_ctx *ctx);
  * the layer-index table (n_steps <= 4096).  The next d3_decode_step must be
  * step 1.  Keeps the cache contents and row count. */
 int d3_set_plan(d3_ctx *ctx, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps);
+
+/* Same, for a schedule the caller made (d3_plan_depth_linear, or any table
+ * d3_plan_from_table accepts): host int32 keep[n_steps], drop_begin[n_steps],
+ * copied.  Step i of d3_decode_step runs the blocks outside step i's window. */
+int d3_set_plan_table(d3_ctx *ctx, const int32_t *keep, const int32_t *drop_begin, int32_t n_steps);
 
 /* Prompt pass (Section 3.1 "initiation phase"; all L blocks, Section 3.2).
  * tokens: dev int32 [B][P].  Writes cache rows [pos_begin, pos_begin + P) of

@@ -38,6 +38,18 @@ def executed_blocks(L: int, alpha_decimal: str, start: int, i: int, min_keep: in
     return [l for l in range(L) if not (s <= l < s + n)]
 
 
+def kept_blocks_linear(L: int, keep_first: int, keep_last: int, n_steps: int, i: int) -> int:
+    """floor of the straight line from keep_first (step 0) to keep_last (step n_steps - 1), in exact rationals."""
+    y = Fraction(keep_first) - Fraction(keep_first - keep_last) * Fraction(i, max(1, n_steps - 1))
+    return y.numerator // y.denominator
+
+
+def executed_blocks_linear(L: int, keep_first: int, keep_last: int, n_steps: int, start: int, i: int) -> List[int]:
+    n = L - kept_blocks_linear(L, keep_first, keep_last, n_steps, i)
+    s = min(start, L - n)
+    return [l for l in range(L) if not (s <= l < s + n)]
+
+
 def _rms(x, gain, eps):
     return x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps) * gain
 
@@ -113,8 +125,9 @@ def forward_all(shape, w64, tokens: Sequence[int], row_blocks: List[Sequence[int
 
 
 def generate(shape, w64, prompt: Sequence[int], G: int, alpha_decimal: str, start: int, min_keep: int = 0,
-             forced: Optional[Sequence[int]] = None):
-    """Greedy D^3 generation with no cache.  Returns (tokens [G], logits [G][V], hidden list)."""
+             forced: Optional[Sequence[int]] = None, step_blocks: Optional[Sequence[Sequence[int]]] = None):
+    """Greedy D^3 generation with no cache.  Returns (tokens [G], logits [G][V], hidden list).
+    step_blocks[i], if given, lists the blocks step i executes instead of the power law's."""
     P = len(prompt)
     all_blocks = list(range(shape.L))
     tokens, logits_all, hidden_all = [], [], []
@@ -123,7 +136,8 @@ def generate(shape, w64, prompt: Sequence[int], G: int, alpha_decimal: str, star
     for i in range(G):
         if i >= 1:
             seq.append(int(forced[i - 1]) if forced is not None else tokens[i - 1])
-            row_blocks = row_blocks + [executed_blocks(shape.L, alpha_decimal, start, i, min_keep)]
+            row_blocks = row_blocks + [list(step_blocks[i]) if step_blocks is not None
+                                       else executed_blocks(shape.L, alpha_decimal, start, i, min_keep)]
         logits, hidden = forward_all(shape, w64, seq, row_blocks)
         tokens.append(int(np.argmax(logits)))
         logits_all.append(logits)

@@ -63,6 +63,33 @@ int d3o_plan_depth(int32_t L, double alpha, int32_t start, int32_t min_keep, int
     return 0;
 }
 
+/* Linear decay between bounds (the comparison schedule named in Section 3.4 / Section 4.1; the bounds are
+ * arguments because the paper prints none): keep[i] = floor(y_i) on the straight line y_i = keep_first -
+ * (keep_first - keep_last) * i / (n_steps - 1), evaluated exactly as one integer quotient (the numerator is
+ * never negative).  Window placement is Table 6's rule, as above. */
+int d3o_plan_depth_linear(int32_t L, int32_t keep_first, int32_t keep_last, int32_t start, int32_t n_steps,
+                          int32_t *keep, int32_t *drop_begin, int32_t *layer_ids)
+{
+    if (L < 1 || keep_last < 0 || keep_last > keep_first || keep_first > L || start < 0 || start >= L || n_steps < 0)
+        return -1;
+    for (int32_t i = 0; i < n_steps; ++i) {
+        int64_t den = n_steps > 1 ? n_steps - 1 : 1;
+        int64_t num = (int64_t)keep_first * den - (int64_t)(keep_first - keep_last) * i;
+        int32_t k = (int32_t)(num / den);
+        int32_t n = L - k;
+        int32_t s = start < L - n ? start : L - n;
+        if (keep) keep[i] = k;
+        if (drop_begin) drop_begin[i] = s;
+        if (layer_ids) {
+            int32_t j = 0;
+            for (int32_t l = 0; l < L; ++l)
+                if (l < s || l >= s + n) layer_ids[(size_t)i * L + j++] = l;
+            for (; j < L; ++j) layer_ids[(size_t)i * L + j] = -1;
+        }
+    }
+    return 0;
+}
+
 /* ---- weights ---- */
 
 static inline real weight_at(const void *w, int32_t dtype, size_t idx)

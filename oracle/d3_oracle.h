@@ -57,6 +57,8 @@ void d3o_set_threads(int n);     /* row-parallel matvec threads (results unchang
  * Returns 0, or -1 on invalid arguments. */
 int d3o_plan_depth(int32_t L, double alpha, int32_t start, int32_t min_keep, int32_t n_steps,
                    int32_t *keep, int32_t *drop_begin, int32_t *layer_ids);
+int d3o_plan_depth_linear(int32_t L, int32_t keep_first, int32_t keep_last, int32_t start, int32_t n_steps,
+                          int32_t *keep, int32_t *drop_begin, int32_t *layer_ids);
 
 /* The model borrows every pointer; they must outlive it. */
 d3o_model *d3o_model_new(const d3o_config *cfg, const void *tok_emb, const d3o_layer *layers,

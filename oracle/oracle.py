@@ -40,6 +40,8 @@ def _lib(variant: str) -> C.CDLL:
         lib.d3o_set_threads.argtypes = [C.c_int]
         lib.d3o_plan_depth.argtypes = [i32, dbl, i32, i32, i32, vp, vp, vp]
         lib.d3o_plan_depth.restype = C.c_int
+        lib.d3o_plan_depth_linear.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp]
+        lib.d3o_plan_depth_linear.restype = C.c_int
         lib.d3o_model_new.argtypes = [C.POINTER(_Config), vp, C.POINTER(_Layer), vp, vp]
         lib.d3o_model_new.restype = vp
         lib.d3o_model_free.argtypes = [vp]
@@ -84,6 +86,17 @@ def plan_depth(L: int, alpha: float, start: int, min_keep: int, n_steps: int, va
     rc = _lib(variant).d3o_plan_depth(L, float(alpha), start, min_keep, n_steps, _ptr(keep), _ptr(drop), _ptr(ids))
     if rc != 0:
         raise ValueError("d3o_plan_depth: invalid arguments")
+    return keep, drop, ids
+
+
+def plan_depth_linear(L: int, keep_first: int, keep_last: int, start: int, n_steps: int, variant: str = "f64"):
+    """Linear decay from keep_first (step 0) to keep_last (last step); same three arrays as plan_depth."""
+    keep = np.zeros(n_steps, np.int32)
+    drop = np.zeros(n_steps, np.int32)
+    ids = np.zeros((n_steps, L), np.int32)
+    rc = _lib(variant).d3o_plan_depth_linear(L, keep_first, keep_last, start, n_steps, _ptr(keep), _ptr(drop), _ptr(ids))
+    if rc != 0:
+        raise ValueError("d3o_plan_depth_linear: invalid arguments")
     return keep, drop, ids
 
 
@@ -191,17 +204,22 @@ class Generation:
 
 def generate(model: OracleModel, prompt: Sequence[int], G: int, alpha: float, start: int, min_keep: int = 0,
              max_seq: Optional[int] = None, forced: Optional[Sequence[int]] = None,
-             seq: Optional[OracleSeq] = None, pos_begin: int = 0, want_hidden: bool = True) -> Generation:
+             seq: Optional[OracleSeq] = None, pos_begin: int = 0, want_hidden: bool = True,
+             plan=None) -> Generation:
     """Prompt pass + G-1 decode steps for one sequence.
 
     forced: if given, token fed at decode step i is forced[i-1] instead of the
     oracle's own T_{i-1} (teacher forcing; logits/tokens are still recorded).
     seq/pos_begin: continue on an existing cache whose rows [0, pos_begin) are set.
+    plan: (keep, drop_begin, layer_ids) of G steps to follow instead of the power law (alpha, start, min_keep).
     """
     L = model.shape.L
     P = len(prompt)
     out = Generation()
-    out.keep, out.drop_begin, out.layer_ids = plan_depth(L, alpha, start, min_keep, max(G, 1), model.variant)
+    if plan is not None:
+        out.keep, out.drop_begin, out.layer_ids = plan
+    else:
+        out.keep, out.drop_begin, out.layer_ids = plan_depth(L, alpha, start, min_keep, max(G, 1), model.variant)
     if seq is None:
         seq = model.new_seq(max_seq or (pos_begin + P + G))
     out.seq = seq

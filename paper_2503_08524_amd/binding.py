@@ -53,11 +53,14 @@ def load_library() -> C.CDLL:
         i32, vp, dbl = C.c_int32, C.c_void_p, C.c_double
         lib.d3_last_error.restype = C.c_char_p
         lib.d3_plan_depth.argtypes = [i32, dbl, i32, i32, i32, vp, vp, vp]
+        lib.d3_plan_depth_linear.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp]
+        lib.d3_plan_from_table.argtypes = [i32, i32, vp, vp, vp]
         lib.d3_workspace_size.argtypes = [C.POINTER(_ModelDesc)]
         lib.d3_workspace_size.restype = C.c_size_t
         lib.d3_create.argtypes = [C.POINTER(vp), C.POINTER(_ModelDesc), C.POINTER(_Weights), vp, vp, vp, C.c_size_t]
         lib.d3_destroy.argtypes = [vp]
         lib.d3_set_plan.argtypes = [vp, dbl, i32, i32, i32]
+        lib.d3_set_plan_table.argtypes = [vp, vp, vp, i32]
         lib.d3_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
         lib.d3_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
         lib.d3_fill_missing_kv.argtypes = [vp, i32, i32, i32, vp]
@@ -87,6 +90,26 @@ def d3_plan_depth(L: int, alpha: float, start_layer: int, min_keep: int, n_steps
     _check(load_library().d3_plan_depth(L, float(alpha), start_layer, min_keep, n_steps,
                                         keep.ctypes.data, drop.ctypes.data, ids.ctypes.data))
     return keep, drop, ids
+
+
+def d3_plan_depth_linear(L: int, keep_first: int, keep_last: int, start_layer: int, n_steps: int):
+    """Linear decay from keep_first to keep_last; same three arrays as d3_plan_depth (host only)."""
+    keep = np.zeros(max(n_steps, 0), np.int32)
+    drop = np.zeros(max(n_steps, 0), np.int32)
+    ids = np.zeros((max(n_steps, 0), max(L, 0)), np.int32)
+    _check(load_library().d3_plan_depth_linear(L, keep_first, keep_last, start_layer, n_steps,
+                                               keep.ctypes.data, drop.ctypes.data, ids.ctypes.data))
+    return keep, drop, ids
+
+
+def d3_plan_from_table(L: int, keep, drop_begin):
+    """layer_ids[n_steps][L] of a caller-made schedule (host only); raises D3Error on a step that does not fit."""
+    keep = np.ascontiguousarray(keep, np.int32); drop = np.ascontiguousarray(drop_begin, np.int32)
+    if keep.shape != drop.shape or keep.ndim != 1:
+        raise ValueError("keep and drop_begin must be 1-d arrays of one length")
+    ids = np.zeros((keep.size, max(L, 0)), np.int32)
+    _check(load_library().d3_plan_from_table(L, keep.size, keep.ctypes.data, drop.ctypes.data, ids.ctypes.data))
+    return ids
 
 
 def _desc(shape, kv_dtype: str, max_batch: int, max_seq: int) -> _ModelDesc:
@@ -157,6 +180,12 @@ class Decoder:
 
     def set_plan(self, alpha: float, start_layer: int, min_keep: int, n_steps: int) -> None:
         _check(self.lib.d3_set_plan(self.ctx, float(alpha), start_layer, min_keep, n_steps))
+
+    def set_plan_table(self, keep, drop_begin) -> None:
+        keep = np.ascontiguousarray(keep, np.int32); drop = np.ascontiguousarray(drop_begin, np.int32)
+        if keep.shape != drop.shape or keep.ndim != 1:
+            raise ValueError("keep and drop_begin must be 1-d arrays of one length")
+        _check(self.lib.d3_set_plan_table(self.ctx, keep.ctypes.data, drop.ctypes.data, keep.size))
 
     def prefill(self, tokens, pos_begin: int = 0, next_tok=None, logits=None, hidden_dump=None):
         """tokens: int32 CUDA tensor [B, P].  Returns next_tok (int32 CUDA tensor [B])."""

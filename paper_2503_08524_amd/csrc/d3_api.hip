@@ -243,6 +243,19 @@ extern "C" int d3_destroy(d3_ctx* ctx) {
 
 extern "C" int32_t d3_n_ctx(const d3_ctx* ctx) { return ctx ? ctx->n_ctx : 0; }
 
+namespace {
+
+int install_plan(d3_ctx* ctx, std::vector<int32_t>& keep, std::vector<int32_t>& drop, std::vector<int32_t>& ids) {
+    D3_HIP(hipMemcpy(ctx->at<int32_t>(ctx->lay.layer_table), ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    ctx->n_steps = (int)keep.size();
+    ctx->keep.swap(keep); ctx->drop_begin.swap(drop); ctx->layer_ids.swap(ids);
+    ctx->has_plan = true;
+    ctx->last_step = 0;
+    return D3_OK;
+}
+
+}  // namespace
+
 extern "C" int d3_set_plan(d3_ctx* ctx, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps) {
     if (!ctx) return fail(D3_EINVAL, "d3_set_plan: ctx is NULL");
     if (n_steps < 1 || n_steps > kMaxPlanSteps) return fail(D3_EINVAL, "d3_set_plan: n_steps must be in [1, %d] (got %d)", kMaxPlanSteps, n_steps);
@@ -250,12 +263,18 @@ extern "C" int d3_set_plan(d3_ctx* ctx, double alpha, int32_t start_layer, int32
     std::vector<int32_t> keep(n_steps), drop(n_steps), ids((size_t)n_steps * L);
     int rc = d3_plan_depth(L, alpha, start_layer, min_keep, n_steps, keep.data(), drop.data(), ids.data());
     if (rc != D3_OK) return rc;
-    D3_HIP(hipMemcpy(ctx->at<int32_t>(ctx->lay.layer_table), ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice));
-    ctx->keep.swap(keep); ctx->drop_begin.swap(drop); ctx->layer_ids.swap(ids);
-    ctx->n_steps = n_steps;
-    ctx->has_plan = true;
-    ctx->last_step = 0;
-    return D3_OK;
+    return install_plan(ctx, keep, drop, ids);
+}
+
+extern "C" int d3_set_plan_table(d3_ctx* ctx, const int32_t* keep_in, const int32_t* drop_begin_in, int32_t n_steps) {
+    if (!ctx) return fail(D3_EINVAL, "d3_set_plan_table: ctx is NULL");
+    if (n_steps < 1 || n_steps > kMaxPlanSteps) return fail(D3_EINVAL, "d3_set_plan_table: n_steps must be in [1, %d] (got %d)", kMaxPlanSteps, n_steps);
+    if (!keep_in || !drop_begin_in) return fail(D3_EINVAL, "d3_set_plan_table: keep and drop_begin must not be NULL");
+    const int L = ctx->desc.n_layers;
+    std::vector<int32_t> keep(keep_in, keep_in + n_steps), drop(drop_begin_in, drop_begin_in + n_steps), ids((size_t)n_steps * L);
+    int rc = d3_plan_from_table(L, n_steps, keep.data(), drop.data(), ids.data());
+    if (rc != D3_OK) return rc;
+    return install_plan(ctx, keep, drop, ids);
 }
 
 namespace {

@@ -21,8 +21,9 @@ def oracle_threads() -> int:
 def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced: Optional[np.ndarray] = None,
                  kv_dtype: Optional[str] = None, max_seq: Optional[int] = None, min_keep: int = 0, fill_each_step: bool = False,
                  decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None, persistent: Optional[bool] = None,
-                 fill_mode: int = 0):
+                 fill_mode: int = 0, linear=None):
     """Prompt pass + G-1 decode steps through the C ABI.  forced: [B][G-1] tokens fed instead of the GPU's own.
+    linear: (keep_first, keep_last) of a linear-decay schedule to follow instead of the power law.
     Returns dict(tokens [G][B], logits [G][B][V], hidden: list of [(k_i+1)][B][d], decoder)."""
     import torch
     from paper_2503_08524_amd import binding
@@ -44,8 +45,12 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
         if persistent is not None:
             assert (decoder.persistent_workgroups > 0) == persistent
     L = shape.L
-    keep, _, _ = binding.d3_plan_depth(L, alpha, start, min_keep, max(G, 2))
-    decoder.set_plan(alpha, start, min_keep, max(G, 2))
+    if linear is not None:
+        keep, drop, _ = binding.d3_plan_depth_linear(L, linear[0], linear[1], start, max(G, 2))
+        decoder.set_plan_table(keep, drop)
+    else:
+        keep, _, _ = binding.d3_plan_depth(L, alpha, start, min_keep, max(G, 2))
+        decoder.set_plan(alpha, start, min_keep, max(G, 2))
     decoder.set_fill_mode(fill_mode)
     toks = torch.from_numpy(np.ascontiguousarray(prompts, np.int32)).to(dev)
     logits = torch.zeros(B, shape.V, dtype=torch.float32, device=dev)
@@ -72,14 +77,15 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
 
 
 def oracle_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced=None, min_keep: int = 0,
-                    max_seq: Optional[int] = None, variant: str = "f64"):
+                    max_seq: Optional[int] = None, variant: str = "f64", linear=None):
     """One oracle Generation per sequence (sequences of a batch are independent and share the schedule)."""
     oracle.set_threads(oracle_threads(), variant)
     model = oracle.OracleModel(shape, w_np, variant)
     gens = []
+    plan = None if linear is None else oracle.plan_depth_linear(shape.L, linear[0], linear[1], start, max(G, 2), variant)
     for b in range(prompts.shape[0]):
         gens.append(oracle.generate(model, prompts[b], G, alpha, start, min_keep=min_keep, max_seq=max_seq,
-                                    forced=None if forced is None else forced[b]))
+                                    forced=None if forced is None else forced[b], plan=plan))
     return model, gens
 
 

@@ -45,6 +45,26 @@ def test_plan_is_bit_exact_against_oracle(lib, L, alpha, start):
             assert (g == r).all()
 
 
+@pytest.mark.parametrize("L,first,last,start", [(32, 32, 8, 0), (32, 32, 17, 31), (40, 36, 4, 24), (80, 80, 0, 48), (4, 4, 1, 2), (32, 20, 20, 5)])
+def test_linear_plan_is_bit_exact_against_oracle_and_survives_the_table_entry(lib, L, first, last, start):
+    for n in (1, 2, 77, 1024):
+        got = d3.d3_plan_depth_linear(L, first, last, start, n)
+        ref = oracle.plan_depth_linear(L, first, last, start, n)
+        for g, r in zip(got, ref):
+            assert (g == r).all()
+        assert (d3.d3_plan_from_table(L, ref[0], ref[1]) == ref[2]).all()
+
+
+def test_plan_table_rejects_steps_that_do_not_fit(lib):
+    for keep, drop in [([5], [0]), ([-1], [0]), ([2], [3]), ([2], [-1]), ([4, 3, 1], [0, 0, 2])]:
+        with pytest.raises(d3.D3Error) as e:
+            d3.d3_plan_from_table(4, keep, drop)
+        assert e.value.status == -1 and "d3_plan_from_table" in str(e.value)
+    assert d3.d3_plan_from_table(4, [4, 3, 0], [4, 3, 0]).tolist() == [[0, 1, 2, 3], [0, 1, 2, -1], [-1, -1, -1, -1]]
+    with pytest.raises(d3.D3Error):
+        d3.d3_plan_depth_linear(8, 9, 2, 0, 4)
+
+
 def test_plan_accepts_null_outputs_and_zero_steps(lib):
     assert lib.d3_plan_depth(8, 0.9, 3, 0, 5, None, None, None) == 0
     assert lib.d3_plan_depth(8, 0.9, 3, 0, 0, None, None, None) == 0

@@ -26,7 +26,8 @@ def _run(shape, B, P, G, alpha, start, kv_dtype=None, forced_seed=None, check_to
     forced = None if forced_seed is None else _forced(B, G, shape.V, forced_seed)
     print(f"case {shape.name} B={B} P={P} G={G} alpha={alpha} start={start} kv={kv_dtype}", flush=True)
     gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, kv_dtype=kv_dtype, **kw)
-    _, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, min_keep=kw.get("min_keep", 0))
+    _, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, min_keep=kw.get("min_keep", 0),
+                                      linear=kw.get("linear"))
     wl, wh = helpers.compare(gpu, gens, G, check_tokens=check_tokens)
     print(f"  worst logit abs err {wl:.3e}, worst hidden rel L2 {wh:.3e}", flush=True)
     return gpu, gens
@@ -37,6 +38,20 @@ def test_tiny_config_tokens_logits_hidden(alpha):
     # the first benchmark configuration in full: fp32 weights, fp32 cache, free-running greedy decoding
     gpu, gens = _run(d3_inputs.TINY, 1, 16, 32, alpha, 2, kv_dtype="f32", check_tokens="all")
     helpers.compare(gpu, gens, 32, check_tokens="all", logit_atol=1e-4, hidden_tol=1e-5)
+
+
+@pytest.mark.parametrize("start", [0, 2, 3])
+def test_tiny_config_linear_decay_shallow_middle_and_deep_first(start):
+    # the comparison schedules (linear decay; windows that grow from the first block, the middle, the last block)
+    # are plans for the same kernels: free-running greedy decoding, tokens identical
+    gpu, gens = _run(d3_inputs.TINY, 1, 16, 32, 1.0, start, kv_dtype="f32", check_tokens="all", linear=(4, 1))
+    helpers.compare(gpu, gens, 32, check_tokens="all", logit_atol=1e-4, hidden_tol=1e-5)
+    assert [h.shape[0] - 1 for h in gpu["hidden"][1:]] == gens[0].keep[1:32].tolist()
+
+
+def test_batched_linear_decay_on_the_matrix_cores():
+    gpu, gens = _run(SMALL_GQA, 5, 21, 12, 1.0, 0, forced_seed=3, linear=(3, 1))
+    gpu, gens = _run(SMALL_BF16, 17, 9, 10, 1.0, 3, forced_seed=4, linear=(4, 0))
 
 
 def test_tiny_config_bf16_cache():

@@ -303,3 +303,21 @@ def test_recompute_fill_definition_and_continuation_match_brute_force(shape, alp
             row_blocks.append(bruteforce.executed_blocks(L, alpha, start, i))
         logits, _ = bruteforce.forward_all(shape, w64, tokens, row_blocks, fill="recompute")
         np.testing.assert_allclose(gen2.logits[i], logits, rtol=0, atol=1e-11)
+
+
+@pytest.mark.parametrize("start", [0, 2, 4])
+def test_oracle_follows_a_linear_plan_like_the_no_cache_brute_force(start):
+    # a schedule other than the power law (linear decay; shallow-first, middle-first and deep-first windows) goes through
+    # the same cache logic: the blocks a step skipped stay out of every later row's attention
+    shape = MICRO
+    w, w64, model = _setup(shape)
+    P, G = 6, 9
+    prompt = d3_inputs.make_prompt(1, P, shape.V, seed=5)[0]
+    plan = oracle.plan_depth_linear(shape.L, shape.L, 1, start, G)
+    gen = oracle.generate(model, prompt, G, 1.0, 0, plan=plan)
+    blocks = [bruteforce.executed_blocks_linear(shape.L, shape.L, 1, G, start, i) for i in range(G)]
+    toks, logits, hidden = bruteforce.generate(shape, w64, prompt, G, "1.0", 0, forced=gen.tokens, step_blocks=blocks)
+    for i in range(G):
+        np.testing.assert_allclose(gen.logits[i], logits[i], rtol=0, atol=1e-11)
+        np.testing.assert_allclose(gen.hidden[i], hidden[i], rtol=0, atol=1e-11)
+    assert [h.shape[0] - 1 for h in gen.hidden] == plan[0][:G].tolist()

@@ -99,3 +99,45 @@ def test_table5_flops_reduction(model, L, avg, printed):
     s = d3_inputs.SHAPES[model]
     r = oracle.flops_reduction(int(L), float(avg), s.d, s.V, s.params_per_block)
     assert abs(r - float(printed)) <= 0.0101, (model, avg, r, printed)
+
+
+# ---------- linear decay between bounds (the comparison schedule of Section 3.4 / Section 4.1) ----------
+
+@pytest.mark.parametrize("L,first,last,n", [(32, 32, 8, 256), (32, 32, 17, 200), (40, 36, 4, 1024), (80, 80, 0, 77), (4, 4, 1, 32),
+                                           (32, 20, 20, 9), (32, 32, 31, 2), (8, 8, 2, 1)])
+def test_linear_keep_matches_exact_rational_line_and_its_invariants(L, first, last, n):
+    keep, drop, ids = oracle.plan_depth_linear(L, first, last, L // 2, n)
+    assert keep.tolist() == [bruteforce.kept_blocks_linear(L, first, last, n, i) for i in range(n)]
+    assert keep[0] == first and (n == 1 or keep[-1] == last)              # the bounds are reached
+    assert (np.diff(keep) <= 0).all()                                     # never deeper later
+    if n > 1:                                                             # never more than one line-step below the line
+        line = first - (first - last) * np.arange(n) / (n - 1)
+        assert ((line - keep >= 0) & (line - keep < 1)).all()
+    for i in range(n):
+        assert ids[i, : keep[i]].tolist() == bruteforce.executed_blocks_linear(L, first, last, n, L // 2, i)
+        assert (ids[i, keep[i]:] == -1).all()
+
+
+def test_linear_is_an_arithmetic_progression_when_the_step_divides():
+    # 32 -> 8 over 25 steps loses exactly one block per step; over 49 steps one block every other step
+    keep, _, _ = oracle.plan_depth_linear(32, 32, 8, 0, 25)
+    assert keep.tolist() == list(range(32, 7, -1))
+    keep, _, _ = oracle.plan_depth_linear(32, 32, 8, 0, 49)
+    assert keep[::2].tolist() == list(range(32, 7, -1)) and (keep[1::2] == keep[2::2]).all()
+    assert keep.sum() * 2 == (32 + 8) * 49 - 24                             # mean of the line minus the 24 half-steps floored away
+
+
+def test_linear_directions_head_first_and_tail_first():
+    L, n = 12, 23
+    keep, drop, ids = oracle.plan_depth_linear(L, 12, 1, 0, n)            # shallow blocks go first
+    for i in range(n):
+        assert ids[i, : keep[i]].tolist() == list(range(L - keep[i], L))
+    keep, drop, ids = oracle.plan_depth_linear(L, 12, 1, L - 1, n)        # deep blocks go first: an early exit
+    for i in range(n):
+        assert ids[i, : keep[i]].tolist() == list(range(keep[i]))
+
+
+def test_linear_plan_rejects_bad_arguments():
+    for args in [(0, 0, 0, 0, 4), (8, 9, 2, 0, 4), (8, 4, 5, 0, 4), (8, 8, -1, 0, 4), (8, 8, 2, 8, 4), (8, 8, 2, -1, 4), (8, 8, 2, 0, -1)]:
+        with pytest.raises(ValueError):
+            oracle.plan_depth_linear(*args)

@@ -42,17 +42,22 @@ CONFIGS = {
     # a long-generation shape beside the benchmark's five: the paper's GSM8K setting (maximum length 1024,
     # alpha = 0.9999, start = 0.2, batch 4 for the 7B model; Section 4.1 and 4.2)
     "7b-long": (d3_inputs.LLAMA_7B, 4, 512, 1024, (0.9999, 1.0), 0.2),
+    # a batch of unequal few-shot prompts, padded on the left to the longest as an evaluation harness batches them
+    # (Section 4.2); every sequence attends to its own rows only
+    "7b-ragged": (d3_inputs.LLAMA_7B, 4, 512, 256, (0.995, 1.0), 0.6),
 }
+RAGGED_LENGTHS = {"7b-ragged": (512, 384, 256, 128)}
 
 
 def block_weight_bytes(s) -> int:
     return s.params_per_block * (4 if s.dtype == "f32" else 2)
 
 
-def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy"):
+def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy", prompt_rows=None):
     """HBM bytes the method must move over decode steps 1..G-1: weights of the executed blocks,
     their KV rows read and appended, the fill of the dropped blocks (COPY: read one row, write it;
-    RECOMPUTE: stream W_k and W_v of every dropped block, write its row), lm_head."""
+    RECOMPUTE: stream W_k and W_v of every dropped block, write its row), lm_head.
+    prompt_rows: prompt rows of the whole batch when the prompts are unequal (default B * P)."""
     wb = block_weight_bytes(s)
     kv_row = 2 * s.H_kv * s.hd * kv_bytes_per_elem          # K + V of one token in one block
     head = s.V * s.d * (4 if s.dtype == "f32" else 2)
@@ -61,7 +66,8 @@ def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy"):
         k, n = int(keep[i]), s.L - int(keep[i])
         per_dropped = {"copy": 2 * kv_row * B, "none": 0,
                        "recompute": 2 * s.H_kv * s.hd * s.d * (4 if s.dtype == "f32" else 2) + kv_row * B}[fill]
-        total += k * (wb + kv_row * B * (P + i) + kv_row * B) + n * per_dropped + head
+        rows = (B * P if prompt_rows is None else prompt_rows) + B * i
+        total += k * (wb + kv_row * rows + kv_row * B) + n * per_dropped + head
     return total
 
 
@@ -158,7 +164,9 @@ def main() -> int:
         dec.set_fill_mode(binding.D3_FILL_RECOMPUTE)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    first_tok = dec.prefill(prompts)
+    lengths = RAGGED_LENGTHS.get(args.config)
+    first_tok = dec.prefill_ragged(prompts, lengths) if lengths else dec.prefill(prompts)
+    prompt_rows = sum(lengths) if lengths else None
     torch.cuda.synchronize()
     prefill_s = time.perf_counter() - t0
 
@@ -169,7 +177,7 @@ def main() -> int:
         run_decode(dec, torch, first_tok, P, G, alpha, start, args.warmup, fill)
         secs = run_decode(dec, torch, first_tok, P, G, alpha, start, args.steps, fill)
         n_tok = args.steps * (G - 1) * B
-        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes, fill) * args.steps
+        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes, fill, prompt_rows) * args.steps
         results[alpha] = {
             "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (args.steps * (G - 1)) * 1e3,
             "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (args.steps * (G - 1)) / 1e9,
@@ -245,7 +253,7 @@ def main() -> int:
         "ms_per_step": head["ms_per_token_step"] * (G - 1), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if shape.dtype == "f32" else "bf16 weights, f32 accumulate, f16 KV cache",
         "data": "synthetic",
-        "config": {"workload": f"{shape.name} B={B} P={P} G={G} alpha={alphas[0]} start_layer={start}",
+        "config": {"workload": f"{shape.name} B={B} P={P if not lengths else list(lengths)} G={G} alpha={alphas[0]} start_layer={start}",
                    "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
                    "persistent_step_workgroups": dec.persistent_workgroups,
                    "fill_every_step": fill},

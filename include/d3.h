@@ -140,6 +140,22 @@ int d3_set_plan_table(d3_ctx *ctx, const int32_t *keep, const int32_t *drop_begi
 int d3_prefill(d3_ctx *ctx, const int32_t *tokens, int32_t B, int32_t P, int32_t pos_begin,
                int32_t *next_tok, float *logits, float *hidden_dump, void *hip_stream);
 
+/* Prompt pass of a batch of unequal prompt lengths (Section 4.2 runs batches of
+ * 4 and 8 few-shot prompts through a harness that pads them on the left to the
+ * longest).  tokens: dev int32 [B][P], sequence b's lengths[b] tokens in columns
+ * [P - lengths[b], P), anything before them (never read); lengths: HOST int32
+ * [B].  Cache rows have the column's number, so every sequence's last prompt
+ * token is row P - 1 and decode steps append one common row; rows below
+ * P - lengths[b] of sequence b are never written nor read, and its rotary
+ * positions count from its first token (position = row - (P - lengths[b])), as
+ * if it had run alone.  The depth schedule stays that of the common step index i
+ * (Section 3.4).  Outputs as d3_prefill; always a fresh request (pos_begin 0);
+ * a later d3_prefill with pos_begin > 0 continues it with B equal tails.
+ * D3_EINVAL unless 1 <= lengths[b] <= P and the longest equals P. */
+int d3_prefill_ragged(d3_ctx *ctx, const int32_t *tokens, const int32_t *lengths, int32_t B,
+                      int32_t P, int32_t *next_tok, float *logits, float *hidden_dump,
+                      void *hip_stream);
+
 /* One decode step (Section 3.1 "generation phase"; Section 3.4).  tok_in: dev
  * int32 [B] = T_{step_i - 1}; runs the keep[step_i] executed blocks of the plan,
  * appends one cache row per sequence in each of them, and writes tok_out: dev

@@ -62,6 +62,7 @@ def load_library() -> C.CDLL:
         lib.d3_set_plan.argtypes = [vp, dbl, i32, i32, i32]
         lib.d3_set_plan_table.argtypes = [vp, vp, vp, i32]
         lib.d3_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        lib.d3_prefill_ragged.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
         lib.d3_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
         lib.d3_fill_missing_kv.argtypes = [vp, i32, i32, i32, vp]
         lib.d3_set_fill_mode.argtypes = [vp, i32]
@@ -194,6 +195,18 @@ class Decoder:
             next_tok = self.torch.empty(B, dtype=self.torch.int32, device=self.device)
         _check(self.lib.d3_prefill(self.ctx, tokens.data_ptr(), B, P, pos_begin, next_tok.data_ptr(), _ptr(logits),
                                    _ptr(hidden_dump), self._stream()))
+        return next_tok
+
+    def prefill_ragged(self, tokens, lengths, next_tok=None, logits=None, hidden_dump=None):
+        """tokens: int32 CUDA tensor [B, P], left-padded; lengths: B host ints (the longest equals P)."""
+        B, P = tokens.shape
+        lens = np.ascontiguousarray(lengths, np.int32)
+        if lens.shape != (B,):
+            raise ValueError("lengths must hold one entry per sequence")
+        if next_tok is None:
+            next_tok = self.torch.empty(B, dtype=self.torch.int32, device=self.device)
+        _check(self.lib.d3_prefill_ragged(self.ctx, tokens.data_ptr(), lens.ctypes.data, B, P, next_tok.data_ptr(),
+                                          _ptr(logits), _ptr(hidden_dump), self._stream()))
         return next_tok
 
     def decode_step(self, tok_in, step_i: int, tok_out, logits=None, hidden_dump=None) -> None:

@@ -201,7 +201,9 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     constexpr int ITMAX = 8;               // loads of K (and of V) in flight per lane
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
+    const int seq = a.cm.seq(c);
+    const int row0 = a.row0 ? a.row0[seq] : 0;         // left-padded batch: this sequence's rows begin here; rows are counted from it
+    const int ctx = a.cm.pos(c) + 1 - row0;
     const int j0 = split * a.split_len;
     const int jend = min(j0 + a.split_len, ctx);
     if (j0 >= jend) return;                // nothing of this column's context falls in this split
@@ -209,7 +211,7 @@ __device__ __forceinline__ void attn_split(const AttnArgs& a, int split, int h0,
     const int j1 = has_new ? ctx - 1 : jend;           // ... and the cache rows of this split end before it
     const int n_live = (ctx + a.split_len - 1) / a.split_len;   // splits of this column that hold rows
     const int kvh = h0 / (a.H / a.H_kv);
-    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const size_t head_off = (((size_t)seq * a.H_kv + kvh) * a.max_seq + row0) * HD;
     const T* Kb = static_cast<const T*>(a.k_cache) + head_off;
     const T* Vb = static_cast<const T*>(a.v_cache) + head_off;
     const int sub = lane % LPR, rg = lane / LPR;
@@ -426,14 +428,16 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
     constexpr int HD = 128;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int seq = a.cm.seq(c), ctx = a.cm.pos(c) + 1;
+    const int seq = a.cm.seq(c);
+    const int row0 = a.row0 ? a.row0[seq] : 0;         // left-padded batch: rows are counted from the sequence's first row
+    const int ctx = a.cm.pos(c) + 1 - row0;
     const int j0 = split * a.split_len;
     const int j1 = min(j0 + a.split_len, ctx);
     if (j0 >= j1) return;
     const bool has_new = ROPE && j1 == ctx;            // the newest row is patched into the staged tiles, not read from the cache
     const int n_live = (ctx + a.split_len - 1) / a.split_len;
     const int kvh = h0 / (a.H / a.H_kv);
-    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const size_t head_off = (((size_t)seq * a.H_kv + kvh) * a.max_seq + row0) * HD;
     const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
     const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
     const float scale = 1.4426950408889634f / sqrtf((float)HD);      // scores in log2 units
@@ -619,19 +623,21 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int c_last = min(c0 + 16 / GH, a.ncols) - 1;               // last column of the tile that exists
-    const int seq = a.cm.seq(c0), ctx_max = a.cm.pos(c_last) + 1;
+    const int seq = a.cm.seq(c0);
+    const int row0 = a.row0 ? a.row0[seq] : 0;         // left-padded batch: rows are counted from the sequence's first row
+    const int ctx_max = a.cm.pos(c_last) + 1 - row0;
     const int j0 = split * a.split_len;
     const int j1 = min(j0 + a.split_len, ctx_max);
     if (j0 >= j1) return;
     const int n_live = (ctx_max + a.split_len - 1) / a.split_len;
     const int kvh = h0 / (a.H / a.H_kv);
-    const size_t head_off = ((size_t)seq * a.H_kv + kvh) * a.max_seq * HD;
+    const size_t head_off = (((size_t)seq * a.H_kv + kvh) * a.max_seq + row0) * HD;
     const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
     const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
     const float scale = 1.4426950408889634f / sqrtf((float)HD);
     const int ci = c0 + i / GH;                                      // this lane's entry: column, head, end of context
     const bool live = ci < a.ncols;
-    const int ctx_i = live ? a.cm.pos(ci) + 1 : 0;
+    const int ctx_i = live ? a.cm.pos(ci) + 1 - row0 : 0;
 
     attn_half8 qhi[4], qlo[4];
     {

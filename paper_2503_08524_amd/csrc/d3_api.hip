@@ -22,7 +22,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, gemm_part, gemm_tickets, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, gemm_part, gemm_tickets, row0, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -86,6 +86,7 @@ Layout make_layout(const d3_model_desc& d) {
     l.h_skip = take(C * d.d_model * 4);
     l.gemm_part = take(kGemmPartBytes);
     l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
+    l.row0 = take(kPassCols * 4);
     l.cand_val = take(4096 * 4);
     l.cand_idx = take(4096 * 4);
     l.total = o;
@@ -114,6 +115,8 @@ struct d3_ctx {
     bool prefilled;
     int B, n_ctx, last_step;
     std::vector<int32_t> row_drop_begin, row_n_drop;   // per cache row: what the step that wrote it dropped
+    bool ragged;                  // left-padded batch: sequence b's rows begin at row0[b] (device copy in the workspace)
+    std::vector<int32_t> row0;
     int fill_mode;                // D3_FILL_RECOMPUTE: decode steps keep the residual that enters their drop window
     int skip_row;                 // cache row whose residual h_skip holds (-1: none)
 
@@ -193,6 +196,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->alu_ok = alu_fits(*desc);
     c->prof_class = D3_K_NONE; c->prof_used = 0;
     c->has_plan = false; c->n_steps = 0;
+    c->ragged = false; c->row0.assign(kPassCols, 0);
     c->prefilled = false; c->B = 0; c->n_ctx = 0; c->last_step = 0;
     c->fill_mode = D3_FILL_COPY;
     c->skip_row = -1;
@@ -358,10 +362,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     const bool rope_in_attn = mfma && ncols <= cm.B;
 
     float2* rope_cs = c->at<float2>(c->lay.rope_cs);
+    const int* row0 = c->ragged ? c->at<int>(c->lay.row0) : nullptr;
     bf16_t *n_hi = c->at<bf16_t>(c->lay.n_hi), *n_lo = c->at<bf16_t>(c->lay.n_lo);   // split of residual * next norm's gain
     float* ssq = c->at<float>(c->lay.ssq);
     int ssq_parts = 1;
-    D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, s));
+    D3_HIP(launch_embed(c->tok_emb, d.weight_dtype, tokens, cm, ncols, dm, d.vocab, x, c->at<double>(c->lay.inv_freq), hd / 2, rope_cs, row0, s));
     auto dump = [&](int slot) -> int {
         if (!hidden_dump) return 0;
         // destination slot layout [dump_total columns][d]; this pass fills columns dump_dst .. dump_dst + dump_cols - 1
@@ -433,6 +438,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         at.out = attn_o; at.out_hi = mfma ? s_hi : nullptr; at.out_lo = mfma ? s_lo : nullptr;
         at.rope_cs = rope_in_attn ? rope_cs : nullptr;
         at.qtile = qtile ? 1 : 0;
+        at.row0 = row0;
         {
             Timed t(c, D3_K_ATTN, s);
             D3_HIP(launch_attention(at, d.kv_dtype, s));
@@ -527,8 +533,12 @@ int decode_persistent(d3_ctx* c, const int32_t* tok_in, int step_i, int32_t* tok
 
 }  // namespace
 
-extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32_t pos_begin, int32_t* next_tok,
-                          float* logits, float* hidden_dump, void* hip_stream) {
+namespace {
+
+// Prompt pass.  lengths (host, optional): a left-padded batch, sequence b holds lengths[b] tokens in columns
+// [P - lengths[b], P) of its row of `tokens` and in the cache rows of the same numbers.
+int prefill_impl(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32_t pos_begin, const int32_t* lengths,
+                 int32_t* next_tok, float* logits, float* hidden_dump, void* hip_stream) {
     if (!ctx || !tokens || !next_tok) return fail(D3_EINVAL, "d3_prefill: NULL argument");
     const d3_model_desc& d = ctx->desc;
     if (B < 1 || B > d.max_batch) return fail(D3_ESHAPE, "d3_prefill: B must be in [1, %d] (got %d)", d.max_batch, B);
@@ -537,17 +547,34 @@ extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t
         return fail(D3_ESTATE, "d3_prefill: pos_begin must be 0 or the current row count %d with the same batch (got %d)", ctx->n_ctx, pos_begin);
     if ((int64_t)pos_begin + P > d.max_seq) return fail(D3_ERANGE, "d3_prefill: rows [%d, %d) exceed max_seq %d", pos_begin, pos_begin + P, d.max_seq);
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (lengths) {
+        int longest = 0;
+        for (int b = 0; b < B; ++b) {
+            if (lengths[b] < 1 || lengths[b] > P) return fail(D3_EINVAL, "d3_prefill_ragged: lengths[%d] = %d is outside [1, %d]", b, lengths[b], P);
+            longest = lengths[b] > longest ? lengths[b] : longest;
+        }
+        if (longest != P) return fail(D3_EINVAL, "d3_prefill_ragged: the longest sequence has %d tokens, P is %d (pad to the longest)", longest, P);
+    }
+    if (pos_begin == 0) {                     // a fresh request decides whether the batch is ragged; a continuation keeps it
+        bool ragged = false;
+        for (int b = 0; b < B; ++b) {
+            ctx->row0[b] = lengths ? P - lengths[b] : 0;
+            ragged = ragged || ctx->row0[b] != 0;
+        }
+        ctx->ragged = ragged;
+        if (ragged) D3_HIP(hipMemcpyAsync(ctx->at<int>(ctx->lay.row0), ctx->row0.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s));
+    }
 
     std::vector<int32_t> all(d.n_layers);
     for (int l = 0; l < d.n_layers; ++l) all[l] = l;
     float* lg = logits ? logits : ctx->at<float>(ctx->lay.logits);
-    if (ctx->prefill_by_seq) {
+    if (ctx->prefill_by_seq || (ctx->ragged && pos_begin == 0)) {
         // one sequence at a time, 32 consecutive positions per pass: the attention of such a chunk reads every cache
         // row once per tile of queries instead of once per query
         // the matrix-core path takes 64 columns a pass (the weights are streamed once per pass)
         const int chunk_cols = ctx->mfma_ok && gemm_mfma_wide_enabled() ? kPassCols : kMaxCols;
         for (int b = 0; b < B; ++b) {
-            for (int base = 0; base < P;) {
+            for (int base = pos_begin == 0 ? ctx->row0[b] : 0; base < P;) {     // padding columns are not computed
                 const int ncols = P - base < chunk_cols ? P - base : chunk_cols;
                 const bool last = base + ncols == P;
                 ColMap cm{base, 1, P, pos_begin, b};
@@ -580,6 +607,19 @@ extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t
     ctx->n_ctx = pos_begin + P;
     ctx->last_step = 0;
     return D3_OK;
+}
+
+}  // namespace
+
+extern "C" int d3_prefill(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32_t pos_begin, int32_t* next_tok,
+                          float* logits, float* hidden_dump, void* hip_stream) {
+    return prefill_impl(ctx, tokens, B, P, pos_begin, nullptr, next_tok, logits, hidden_dump, hip_stream);
+}
+
+extern "C" int d3_prefill_ragged(d3_ctx* ctx, const int32_t* tokens, const int32_t* lengths, int32_t B, int32_t P,
+                                 int32_t* next_tok, float* logits, float* hidden_dump, void* hip_stream) {
+    if (!lengths) return fail(D3_EINVAL, "d3_prefill_ragged: lengths is NULL");
+    return prefill_impl(ctx, tokens, B, P, 0, lengths, next_tok, logits, hidden_dump, hip_stream);
 }
 
 extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits,

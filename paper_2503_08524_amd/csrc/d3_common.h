@@ -124,9 +124,10 @@ int launch_gain_split(const float* x, int x_stride, const float* gain, int K, in
                       bf16_t* hi, bf16_t* lo, float* ssq, hipStream_t s);
 
 // ---------------- the rest of a block ----------------
-// x[c][:] = E[token(c)][:], and the pass's rotary table rope_cs[c][j] = (cos, sin)(pos(c) * inv_freq[j])
+// x[c][:] = E[token(c)][:], and the pass's rotary table rope_cs[c][j] = (cos, sin)((pos(c) - row0[seq(c)]) * inv_freq[j])
+// (row0 optional: the first cache row of each sequence of a left-padded batch)
 int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
-                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, hipStream_t s);
+                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, const int* row0, hipStream_t s);
 
 struct RopeArgs {
     float* qkv;            // [ncols][(H + 2 H_kv) * hd] fp32: q rotated in place
@@ -141,6 +142,7 @@ int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s);
 struct AttnArgs {
     const float* q;        // [ncols][q_stride]: q heads, then (rope_cs set) the newest k and v rows; rotated unless rope_cs is set
     const float2* rope_cs; // optional [ncols][hd/2] (cos, sin): rotate q and k here and append the newest K/V row
+    const int* row0;       // optional [B]: first cache row of each sequence (a left-padded batch); rows below it are never read
     int qtile;             // the columns are consecutive positions of one sequence (a prompt chunk): tiles of queries share the cache rows
     int q_stride;
     const void* k_cache;   // this block's cache

@@ -11,11 +11,12 @@ template <typename W>
 __global__ __launch_bounds__(256) void embed_kernel(const W* __restrict__ emb, const int32_t* __restrict__ tokens,
                                                     ColMap cm, int d, int vocab, float* __restrict__ x,
                                                     const double* __restrict__ inv_freq, int half_hd,
-                                                    float2* __restrict__ rope_cs) {
+                                                    float2* __restrict__ rope_cs, const int* __restrict__ row0) {
     const int c = blockIdx.x;
     if ((int)threadIdx.x < half_hd) {       // the rotation angles depend on the position only, not on the block
         double sn, cs;
-        sincos((double)cm.pos(c) * inv_freq[threadIdx.x], &sn, &cs);
+        const int pos = cm.pos(c) - (row0 ? row0[cm.seq(c)] : 0);      // a left-padded sequence counts from its first token
+        sincos((double)pos * inv_freq[threadIdx.x], &sn, &cs);
         rope_cs[(size_t)c * half_hd + threadIdx.x] = make_float2((float)cs, (float)sn);
     }
     int tok = tokens[cm.tok_index(c)];
@@ -184,13 +185,13 @@ __global__ __launch_bounds__(64) void fill_kernel(FillArgs a, int bytes_per_vec)
 }  // namespace
 
 int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
-                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, hipStream_t s) {
+                 int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, const int* row0, hipStream_t s) {
     if (weight_dtype == 0)
         hipLaunchKernelGGL(embed_kernel<float>, dim3(ncols), dim3(256), 0, s, static_cast<const float*>(tok_emb), tokens, cm, d, vocab, x,
-                           inv_freq, half_hd, rope_cs);
+                           inv_freq, half_hd, rope_cs, row0);
     else
         hipLaunchKernelGGL(embed_kernel<bf16_t>, dim3(ncols), dim3(256), 0, s, static_cast<const bf16_t*>(tok_emb), tokens, cm, d, vocab, x,
-                           inv_freq, half_hd, rope_cs);
+                           inv_freq, half_hd, rope_cs, row0);
     return (int)hipGetLastError();
 }
 

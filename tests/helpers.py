@@ -21,9 +21,10 @@ def oracle_threads() -> int:
 def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced: Optional[np.ndarray] = None,
                  kv_dtype: Optional[str] = None, max_seq: Optional[int] = None, min_keep: int = 0, fill_each_step: bool = False,
                  decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None, persistent: Optional[bool] = None,
-                 fill_mode: int = 0, linear=None):
+                 fill_mode: int = 0, linear=None, lengths=None):
     """Prompt pass + G-1 decode steps through the C ABI.  forced: [B][G-1] tokens fed instead of the GPU's own.
     linear: (keep_first, keep_last) of a linear-decay schedule to follow instead of the power law.
+    lengths: [B] prompt lengths of a left-padded batch (prompts[b, P - lengths[b]:] are sequence b's tokens).
     Returns dict(tokens [G][B], logits [G][B][V], hidden: list of [(k_i+1)][B][d], decoder)."""
     import torch
     from paper_2503_08524_amd import binding
@@ -55,7 +56,10 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
     toks = torch.from_numpy(np.ascontiguousarray(prompts, np.int32)).to(dev)
     logits = torch.zeros(B, shape.V, dtype=torch.float32, device=dev)
     hid = torch.zeros(L + 1, B, shape.d, dtype=torch.float32, device=dev)
-    cur = decoder.prefill(toks, pos_begin=pos_begin, logits=logits, hidden_dump=hid)
+    if lengths is not None:
+        cur = decoder.prefill_ragged(toks, lengths, logits=logits, hidden_dump=hid)
+    else:
+        cur = decoder.prefill(toks, pos_begin=pos_begin, logits=logits, hidden_dump=hid)
     out_tokens = [cur.cpu().numpy().copy()]
     out_logits = [logits.cpu().numpy().copy()]
     out_hidden = [hid.cpu().numpy().copy()]
@@ -77,14 +81,15 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
 
 
 def oracle_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced=None, min_keep: int = 0,
-                    max_seq: Optional[int] = None, variant: str = "f64", linear=None):
+                    max_seq: Optional[int] = None, variant: str = "f64", linear=None, lengths=None):
     """One oracle Generation per sequence (sequences of a batch are independent and share the schedule)."""
     oracle.set_threads(oracle_threads(), variant)
     model = oracle.OracleModel(shape, w_np, variant)
     gens = []
     plan = None if linear is None else oracle.plan_depth_linear(shape.L, linear[0], linear[1], start, max(G, 2), variant)
     for b in range(prompts.shape[0]):
-        gens.append(oracle.generate(model, prompts[b], G, alpha, start, min_keep=min_keep, max_seq=max_seq,
+        own = prompts[b] if lengths is None else prompts[b, prompts.shape[1] - int(lengths[b]):]   # a sequence knows nothing of its padding
+        gens.append(oracle.generate(model, own, G, alpha, start, min_keep=min_keep, max_seq=max_seq,
                                     forced=None if forced is None else forced[b], plan=plan))
     return model, gens
 

@@ -152,17 +152,18 @@ def test_decode_is_deterministic_and_rewind_reproduces_it():
         assert (t0 == t1).all() and (l0 == l1).all()                              # bit-identical replays
 
 
-def _check_recomputed_rows(dec, gens, shape, P, G, tol):
+def _check_recomputed_rows(dec, gens, shape, P, G, tol, lengths=None):
     L = shape.L
     worst = 0.0
     for b, gen in enumerate(gens):
-        oracle.fill_generated_rows(gen, P, G, mode="recompute")
+        own = P if lengths is None else int(lengths[b])      # the oracle's sequence knows nothing of its padding
+        oracle.fill_generated_rows(gen, own, G, mode="recompute")
         for i in range(1, G):
             pos = P + i - 1
             s, n = int(gen.drop_begin[i]), L - int(gen.keep[i])
             for l in range(s, s + n):
                 kg, vg = _cache_rows(dec, l, b, pos)
-                ko, vo = gen.seq.get_kv(l, pos)
+                ko, vo = gen.seq.get_kv(l, own + i - 1)
                 ek = np.abs(kg - ko).max() / max(1.0, np.abs(ko).max())
                 ev = np.abs(vg - vo).max() / max(1.0, np.abs(vo).max())
                 worst = max(worst, ek, ev)
@@ -199,6 +200,41 @@ def test_recompute_fill_matches_oracle_and_continuation_reads_it(B, start, kv):
              for b, gen in enumerate(gens)]
     wl, wh = helpers.compare(gpu2, gens2, G2)
     print(f"  worst recomputed row err {worst:.3e}; continuation logit abs err {wl:.3e}, hidden {wh:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("mode", ["copy", "recompute"])
+def test_left_padded_batch_fill_and_continuation(mode):
+    """A ragged batch: the fill of each sequence's dropped blocks and a second request on the same cache (equal tails)
+    against per-sequence oracles that know nothing of the padding."""
+    import torch
+    from paper_2503_08524_amd import binding
+    shape, alpha, start, kv = SHAPE, 0.8, 2, "f16"
+    lengths = np.array([6, 2, 5], np.int32)
+    B, P, G, P2, G2 = 3, 6, 9, 4, 4
+    w = d3_inputs.make_weights(shape, 2)
+    prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)
+    prompts2 = d3_inputs.make_prompt(B, P2, shape.V, seed=5)
+    forced2 = d3_inputs.make_prompt(B, G2 - 1, shape.V, seed=6)
+    max_seq = P + G + P2 + G2
+    print(f"case ragged fill {mode}", flush=True)
+    fm = binding.D3_FILL_RECOMPUTE if mode == "recompute" else binding.D3_FILL_COPY
+    gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, kv_dtype=kv, fill_each_step=True,
+                               max_seq=max_seq, fill_mode=fm, lengths=lengths)
+    dec = gpu["decoder"]
+    torch.cuda.synchronize()
+    model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq, lengths=lengths)
+    helpers.compare(gpu, gens, G)
+    if mode == "recompute":
+        _check_recomputed_rows(dec, gens, shape, P, G, 4e-3, lengths=lengths)
+    else:
+        for b, gen in enumerate(gens):
+            oracle.fill_generated_rows(gen, int(lengths[b]), G)
+    gpu2 = helpers.gpu_generate(shape, w, prompts2, G2, alpha, start, forced=forced2, decoder=dec, pos_begin=P + G - 1)
+    gens2 = [oracle.generate(model, prompts2[b], G2, alpha, start, seq=gen.seq, pos_begin=int(lengths[b]) + G - 1, forced=forced2[b])
+             for b, gen in enumerate(gens)]
+    wl, wh = helpers.compare(gpu2, gens2, G2)
+    print(f"  continuation logit abs err {wl:.3e}, hidden {wh:.3e}", flush=True)
 
 
 @pytest.mark.parametrize("name,B", [("llama-7b", 1), ("llama-70b", 2)])

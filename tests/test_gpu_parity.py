@@ -27,7 +27,7 @@ def _run(shape, B, P, G, alpha, start, kv_dtype=None, forced_seed=None, check_to
     print(f"case {shape.name} B={B} P={P} G={G} alpha={alpha} start={start} kv={kv_dtype}", flush=True)
     gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, kv_dtype=kv_dtype, **kw)
     _, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, min_keep=kw.get("min_keep", 0),
-                                      linear=kw.get("linear"))
+                                      linear=kw.get("linear"), lengths=kw.get("lengths"))
     wl, wh = helpers.compare(gpu, gens, G, check_tokens=check_tokens)
     print(f"  worst logit abs err {wl:.3e}, worst hidden rel L2 {wh:.3e}", flush=True)
     return gpu, gens
@@ -52,6 +52,25 @@ def test_tiny_config_linear_decay_shallow_middle_and_deep_first(start):
 def test_batched_linear_decay_on_the_matrix_cores():
     gpu, gens = _run(SMALL_GQA, 5, 21, 12, 1.0, 0, forced_seed=3, linear=(3, 1))
     gpu, gens = _run(SMALL_BF16, 17, 9, 10, 1.0, 3, forced_seed=4, linear=(4, 0))
+
+
+@pytest.mark.parametrize("shape,lengths,kv", [
+    (d3_inputs.TINY, (16, 5, 11), "f32"),                 # fp32 weights: vector-ALU projections, one column per launch group
+    (SMALL_BF16, (9, 70, 1, 33, 64), None),               # head_dim 64: vector-ALU attention; chunks of 64 + 6 columns
+    (SMALL_GQA, (130, 17, 77, 130), "f16"),               # head_dim 128, f16 cache: query tiles in the prompt, MFMA attention in decode
+    (SMALL_GQA, (40, 3), "bf16"),
+])
+def test_left_padded_batch_of_unequal_prompts(shape, lengths, kv):
+    # every sequence of a ragged batch must behave as if it had run alone: its own positions, its own context
+    B, P = len(lengths), max(lengths)
+    _run(shape, B, P, 9, 0.8, 1, kv_dtype=kv, forced_seed=21, lengths=np.array(lengths, np.int32), max_seq=P + 9)
+
+
+def test_left_padded_batch_spans_attention_splits():
+    # the short sequence's rows begin inside a later split: the splits below it hold nothing of it
+    lengths = np.array([700, 150, 699], np.int32)
+    _run(SMALL_GQA, 3, 700, 6, 0.7, 1, forced_seed=22, lengths=lengths)
+    _run(SMALL_BF16, 2, 650, 4, 0.9, 2, forced_seed=23, lengths=np.array([40, 650], np.int32))
 
 
 def test_tiny_config_bf16_cache():

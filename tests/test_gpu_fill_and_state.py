@@ -106,6 +106,10 @@ def test_call_order_and_range_errors():
     assert status(lambda: dec.prefill(torch.zeros(3, 4, dtype=torch.int32, device="cuda:0"))) == -2   # batch > max_batch
     assert status(lambda: dec.prefill(torch.zeros(2, 13, dtype=torch.int32, device="cuda:0"))) == -3  # beyond max_seq
     assert status(lambda: dec.prefill(prompts, pos_begin=3)) == -4                 # neither 0 nor the row count
+    assert status(lambda: dec.prefill_ragged(prompts, [0, 8])) == -1               # an empty sequence
+    assert status(lambda: dec.prefill_ragged(prompts, [9, 8])) == -1               # longer than the padded width
+    assert status(lambda: dec.prefill_ragged(prompts, [7, 5])) == -1               # not padded to the longest
+    assert status(lambda: dec.set_plan_table([6, 7], [0, 0])) == -1                # keeps more blocks than there are
     dec.prefill(prompts)
     assert dec.n_ctx == 8
     assert status(lambda: dec.decode_step(tok, 2, out)) == -4                      # steps must come in order
@@ -288,10 +292,11 @@ def test_recompute_fill_call_rules():
 
 
 def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split():
-    """A second prompt that starts at row 61: its chunk's query tiles (4 queries x 4 heads of a KV head at this shape) are
-    not aligned with the 64-row context splits, so some queries of a tile have no row in the last split while others do."""
+    """A second prompt that starts at row 125: its chunk's query tiles (4 queries x 4 heads of a KV head at this shape) are
+    not aligned with the context splits (multiples of 64 rows, 128 by default), so some queries of a tile have no row in
+    the last split while others do."""
     shape = ModelShape("small-gqa", L=3, d=512, H=8, H_kv=2, hd=128, F=1376, V=2000, dtype="bf16")
-    B, P, G, alpha, start = 2, 50, 12, 0.9, 1
+    B, P, G, alpha, start = 2, 114, 12, 0.9, 1
     P2, G2 = 10, 3
     w = d3_inputs.make_weights(shape, 3)
     prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
@@ -303,7 +308,7 @@ def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split():
     gpu = helpers.gpu_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq, fill_each_step=True)
     dec = gpu["decoder"]
     n_rows = P + G - 1
-    assert n_rows == 61
+    assert n_rows == 125
     gpu2 = helpers.gpu_generate(shape, w, prompts2, G2, alpha, start, forced=forced2, decoder=dec, pos_begin=n_rows)
     model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq)
     gens2 = []

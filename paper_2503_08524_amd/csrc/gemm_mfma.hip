@@ -321,6 +321,9 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* 
         // a gate/up pair doubles the bytes a wave keeps in flight: with workgroups to spare (>= 3 per CU at RT = 2)
         // one tile pair per wave ran faster (70B shape: 160 vs 176 us)
         if (!rt_forced && mode == MODE_SWIGLU && rt == 2 && tiles / 2 >= 3 * n_cu) continue;
+        // ... and with too few of them (under 1.5 per CU) two pairs per wave starve the memory system
+        // (7B shape, 4 columns: 344 workgroups 44.6 us, 688 of one pair 34.4 us; 13B shape: 432 of two pairs 50.1 us, 864 of one 52.8 us)
+        if (!rt_forced && mode == MODE_SWIGLU && rt == 2 && 2 * (tiles / 2) < 3 * n_cu) continue;
         if (rt_forced ? rt <= rt_forced : (10 * (tiles / rt) >= 6 * n_cu && (long long)(tiles / rt) * waves >= 4LL * n_cu)) break;
     }
     if (n_groups) *n_groups = tiles / best_rt;

@@ -196,7 +196,8 @@ int32_t d3_n_ctx(const d3_ctx *ctx);
 /* Forget cache rows [n_rows, n_ctx): the next decode step writes row n_rows.
  * Used to re-run the generation phase on the same prompt (Section 3.1) without a
  * new prompt pass.  Resets the step counter (next decode step is 1).  Host only.
- * D3_ERANGE unless 1 <= n_rows <= n_ctx. */
+ * D3_ERANGE unless 1 <= n_rows <= n_ctx (and, after d3_prefill_ragged, n_rows
+ * lies above every sequence's first row). */
 int d3_truncate(d3_ctx *ctx, int32_t n_rows);
 
 /* Measurement aid: per-launch timing of one kernel class with HIP events recorded

@@ -745,6 +745,9 @@ extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
     if (!ctx) return fail(D3_EINVAL, "d3_truncate: ctx is NULL");
     if (!ctx->prefilled) return fail(D3_ESTATE, "d3_truncate: no prompt pass yet");
     if (n_rows < 1 || n_rows > ctx->n_ctx) return fail(D3_ERANGE, "d3_truncate: n_rows must be in [1, %d] (got %d)", ctx->n_ctx, n_rows);
+    if (ctx->ragged)                           // every sequence of a left-padded batch keeps at least its first row
+        for (int b = 0; b < ctx->B; ++b)
+            if (n_rows <= ctx->row0[b]) return fail(D3_ERANGE, "d3_truncate: sequence %d of the ragged batch begins at row %d (got n_rows %d)", b, ctx->row0[b], n_rows);
     ctx->n_ctx = n_rows;
     ctx->last_step = 0;
     ctx->skip_row = -1;

@@ -52,8 +52,11 @@ __device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32
 
 // grid: (row groups of W * RT tiles, K slices).  CT column tiles (2: up to 32 columns, 4 waves per workgroup; 4: up to
 // 64 columns, 8 waves per workgroup, so that the bigger panel is shared by more row tiles).
+// A gate/up pair of tiles per wave wants 204 registers (two waves per SIMD); its launch has 2.7 workgroups per CU, so at that
+// size the last quarter of them starts only when the first ones have finished (entry times up to 24 us into a 42 us
+// launch).  Held to three waves per SIMD (168 registers, 33 spilled) every workgroup starts at once: 42 -> 38 us.
 template <int MODE, int RT, int CT, int W>
-__global__ __launch_bounds__(W * 64) void gemm_wide_kernel(GemvArgs a) {
+__global__ __launch_bounds__(W * 64, (MODE == MODE_SWIGLU && CT == 2) ? 3 : 1) void gemm_wide_kernel(GemvArgs a) {
     constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;
     constexpr int NA = RT * SW;                        // A tiles per wave and turn
     constexpr int NB = 2 * CT;                         // panel tiles: hi, lo of every column tile

@@ -411,6 +411,22 @@ typedef _Float16 attn_half8 __attribute__((ext_vector_type(8)));
 typedef float attn_f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kAttnPitch = 272;            // bytes per staged row of 128 halves (+16: conflict-free fragment reads)
 
+// B fragment of P.V for head-dim columns 16 nt .. 16 nt + 15 from a staged 32-row V tile: lane (i, g) gets column
+// 16 nt + i of rows 4g..4g+3 and 16+4g..16+4g+3 (the row numbering the score tiles leave P in).  The contraction index
+// is the tile's slow index, so each half is one LDS transpose read: inside a group of 16 lanes, lane s points at four
+// consecutive columns (4 (s % 4)) of row s / 4, and lane i receives column i of those four rows.
+typedef short attn_short4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ attn_half8 attn_v_fragment(const char* vbuf, int nt, int lane) {
+    const int s = lane & 15, g = lane >> 4;
+    const char* p = vbuf + (4 * g + (s >> 2)) * kAttnPitch + (16 * nt + 4 * (s & 3)) * 2;
+    typedef __attribute__((address_space(3))) attn_short4 lds_short4;
+    const attn_short4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(p));
+    const attn_short4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4*)(p + 16 * kAttnPitch));
+    typedef short attn_short8 __attribute__((ext_vector_type(8)));
+    const attn_short8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(attn_half8, both);
+}
+
 template <int NW, int G>
 struct AttnMfmaShared {
     union {
@@ -585,12 +601,7 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
-            attn_half8 vb;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int row = j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4);
-                vb[j] = *reinterpret_cast<const f16_t*>(vbuf + row * kAttnPitch + (16 * nt + i) * 2);
-            }
+            const attn_half8 vb = attn_v_fragment(vbuf, nt, lane);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
         }
@@ -666,20 +677,20 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
     const int lrow = lane >> 4, lseg = lane & 15;
 
     for (int r0 = j0 + wave * 32; r0 < j1; r0 += NW * 32) {
-        uint4 kreg[2][4], vreg[8];
+        u32x4 kreg[8], vreg[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
             int row = r0 + 4 * q + lrow;
             row = row < j1 ? row : j1 - 1;
-            kreg[q >> 2][q & 3] = *reinterpret_cast<const uint4*>(Kb + (size_t)row * HD + 8 * lseg);   // re-read by the next tiles: cached
-            vreg[q] = *reinterpret_cast<const uint4*>(Vb + (size_t)row * HD + 8 * lseg);
+            kreg[q] = *reinterpret_cast<const u32x4*>(Kb + (size_t)row * HD + 8 * lseg);   // re-read by the next tiles: cached
+            vreg[q] = *reinterpret_cast<const u32x4*>(Vb + (size_t)row * HD + 8 * lseg);
         }
         attn_f32x4 S[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<uint4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[t][q];
+                *reinterpret_cast<u32x4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[4 * t + q];
             __builtin_amdgcn_wave_barrier();
             S[t] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -721,18 +732,13 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
         if (g == 0) keepbuf[i] = keep;
 #pragma unroll
         for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<uint4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
+            *reinterpret_cast<u32x4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
         __builtin_amdgcn_wave_barrier();
         const float4 kf = *reinterpret_cast<const float4*>(keepbuf + 4 * g);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
-            attn_half8 vb;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int row = j < 4 ? 4 * g + j : 16 + 4 * g + (j - 4);
-                vb[j] = *reinterpret_cast<const f16_t*>(vbuf + row * kAttnPitch + (16 * nt + i) * 2);
-            }
+            const attn_half8 vb = attn_v_fragment(vbuf, nt, lane);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
         }

@@ -131,21 +131,48 @@ __global__ __launch_bounds__(W * 64, (MODE == MODE_SWIGLU && CT == 2) ? 3 : 1) v
         constexpr int SLOT = decltype(slot_c)::value;
         const int buf = (t - t_begin) & 1;
         const char* pan = panel[buf];
+        auto b_frag = [&](int tile, int u) {
+            return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(pan + tile * kTile + (lane & 15) * kPitch + u * 64 + (lane >> 4) * 16));
+        };
+        if constexpr (NA > 1 && CT >= 4) {
+            // every A tile of the turn becomes fragments first, so that a panel fragment is read from LDS once and used for
+            // all of them: with four column tiles the panel reads are most of the LDS traffic, and the LDS pipe, not HBM,
+            // sets the pace of a turn (gate/up at 64 columns: 58.8 -> 49.7 us).  With two column tiles the 16 extra
+            // registers cost more than the reads (batch-32 gate/up: 42.5 -> 50 us), so that shape keeps the order below.
+            u32x4 af[NA][U];
 #pragma unroll
-        for (int r = 0; r < NA; ++r) {
-            u32x4 af[U];
-            tile_to_frags(ga[SLOT][r], atile, af);
-            if (decltype(a_issue)::value) tile_load(ga[SLOT][r], wrow[r], K, (t + 2) * (U * 32), K);
+            for (int r = 0; r < NA; ++r) {
+                tile_to_frags(ga[SLOT][r], atile, af[r]);
+                if (decltype(a_issue)::value) tile_load(ga[SLOT][r], wrow[r], K, (t + 2) * (U * 32), K);
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 if (t * U + u < nks) {
-                    const bf16x8 wa = __builtin_bit_cast(bf16x8, af[u]);
 #pragma unroll
                     for (int tt = 0; tt < CT; ++tt) {
-                        const u32x4 bh = *reinterpret_cast<const u32x4*>(pan + (2 * tt) * kTile + (lane & 15) * kPitch + u * 64 + (lane >> 4) * 16);
-                        const u32x4 bl = *reinterpret_cast<const u32x4*>(pan + (2 * tt + 1) * kTile + (lane & 15) * kPitch + u * 64 + (lane >> 4) * 16);
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bh), acc[r][tt], 0, 0, 0);
-                        acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8, bl), acc[r][tt], 0, 0, 0);
+                        const bf16x8 bh = b_frag(2 * tt, u), bl = b_frag(2 * tt + 1, u);
+#pragma unroll
+                        for (int r = 0; r < NA; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[r][u]), bh, acc[r][tt], 0, 0, 0);
+#pragma unroll
+                        for (int r = 0; r < NA; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, af[r][u]), bl, acc[r][tt], 0, 0, 0);
+                    }
+                }
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < NA; ++r) {
+                u32x4 af[U];
+                tile_to_frags(ga[SLOT][r], atile, af);
+                if (decltype(a_issue)::value) tile_load(ga[SLOT][r], wrow[r], K, (t + 2) * (U * 32), K);
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (t * U + u < nks) {
+                        const bf16x8 wa = __builtin_bit_cast(bf16x8, af[u]);
+#pragma unroll
+                        for (int tt = 0; tt < CT; ++tt) {
+                            acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, b_frag(2 * tt, u), acc[r][tt], 0, 0, 0);
+                            acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, b_frag(2 * tt + 1, u), acc[r][tt], 0, 0, 0);
+                        }
                     }
                 }
             }
@@ -340,7 +367,10 @@ int launch_one(const GemvArgs& a, int groups, int ks, hipStream_t s) {
 
 template <int MODE>
 int launch_rt(const GemvArgs& a, int ct, int rt, int groups, int ks, hipStream_t s) {
-    if (ct == 4) return launch_one<MODE, 1, 4, 8>(a, groups, ks, s);
+    if (ct == 4) {
+        if constexpr (MODE != MODE_SWIGLU) { if (rt == 2) return launch_one<MODE, 2, 4, 8>(a, groups, ks, s); }
+        return launch_one<MODE, 1, 4, 8>(a, groups, ks, s);
+    }
     if (rt == 2) {
         if constexpr (MODE == MODE_SWIGLU) return (int)hipErrorInvalidValue;
         else return launch_one<MODE, 2, 2, 4>(a, groups, ks, s);
@@ -362,7 +392,11 @@ int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, 
     const int ct = a.ncols > 32 ? 4 : 2;               // column tiles
     const int w = ct == 4 ? 8 : 4;                     // waves per workgroup
     int rt = 1;
-    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (ct == 2 && (v == 1 || mode != MODE_SWIGLU)) rt = v;
+    // 64 columns, one stacked matrix (QKV, lm_head): two row tiles per wave share the panel fragments and put the whole
+    // launch on the chip at once (7B QKV: 240 workgroups, 37.8 -> 30.9 us); the residual projections have too few row
+    // tiles for that (down-projection: 128 workgroups, 32.6 -> 44 us)
+    if (ct == 4 && mode == MODE_STORE) rt = 2;
+    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (v == 1 || mode != MODE_SWIGLU) rt = v;
     int groups = (tiles + w * rt - 1) / (w * rt);
     // up to 32 columns: three workgroups fit a CU; up to 64: one (its panels fill most of the LDS)
     int ks = (ct == 4 ? 2 : 3) * n_cu / groups;

@@ -110,6 +110,10 @@ def test_call_order_and_range_errors():
     assert status(lambda: dec.prefill_ragged(prompts, [9, 8])) == -1               # longer than the padded width
     assert status(lambda: dec.prefill_ragged(prompts, [7, 5])) == -1               # not padded to the longest
     assert status(lambda: dec.set_plan_table([6, 7], [0, 0])) == -1                # keeps more blocks than there are
+    dec.prefill_ragged(prompts, [8, 5])
+    assert status(lambda: dec.truncate(3)) == -3                                   # sequence 1 begins at row 3: it would keep no row
+    dec.truncate(4)
+    assert dec.n_ctx == 4
     dec.prefill(prompts)
     assert dec.n_ctx == 8
     assert status(lambda: dec.decode_step(tok, 2, out)) == -4                      # steps must come in order

@@ -102,19 +102,22 @@ def cpu_baseline(shape, keep_mean):
     w = d3_inputs.make_weights(s1, 0)
     model = oracle.OracleModel(s1, w, "f32")
     oracle.set_threads(1, "f32")
-    seq = model.new_seq(8)
-    toks = d3_inputs.make_prompt(1, 6, s1.V, seed=3)[0]
-    t0 = time.perf_counter()
-    for p in range(4):
-        seq.forward_token(int(toks[p]), p, [0])
-    t_block = (time.perf_counter() - t0) / 4
-    t0 = time.perf_counter()
-    for p in range(4, 6):
-        seq.forward_token(int(toks[p]), p, [], want_logits=True)
-    t_head = (time.perf_counter() - t0) / 2
+    cap = 256                                   # a bounded sample: about 9 s of block steps and 3 s of lm_head passes
+    seq = model.new_seq(2 * cap)
+    toks = d3_inputs.make_prompt(1, 2 * cap, s1.V, seed=3)[0]
+    n_block, t0 = 0, time.perf_counter()
+    while n_block < cap and (n_block < 4 or time.perf_counter() - t0 < 9.0):
+        seq.forward_token(int(toks[n_block]), n_block, [0])
+        n_block += 1
+    t_block = (time.perf_counter() - t0) / n_block
+    n_head, t0 = 0, time.perf_counter()
+    while n_head < cap and (n_head < 2 or time.perf_counter() - t0 < 3.0):
+        seq.forward_token(int(toks[n_block + n_head]), n_block + n_head, [], want_logits=True)
+        n_head += 1
+    t_head = (time.perf_counter() - t0) / n_head
     per_tok = keep_mean * t_block + t_head
     return {"value": 1.0 / per_tok, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-            "sample": f"float32 oracle, 1 thread, {s1.name}: 4 block-steps ({t_block * 1e3:.0f} ms each) + 2 lm_head "
+            "sample": f"float32 oracle, 1 thread, {s1.name}: {n_block} block-steps ({t_block * 1e3:.0f} ms each) + {n_head} lm_head "
                       f"passes ({t_head * 1e3:.0f} ms each), extrapolated to {keep_mean:.2f} blocks/token",
             "host_cores_available": os.cpu_count()}
 

@@ -160,6 +160,15 @@ def main() -> int:
     cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
     cal_dst.copy_(cal_src)
     torch.cuda.synchronize()
+    # the same copy, timed: what a plain streaming kernel reaches on this chip (bytes read + bytes written per second),
+    # the ceiling that the fractions of the nominal 8 TB/s can be held against
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        cal_dst.copy_(cal_src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del cal_src, cal_dst
 
     dec.set_plan(alphas[0], start, 0, G)
@@ -185,6 +194,7 @@ def main() -> int:
             "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (args.steps * (G - 1)) * 1e3,
             "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (args.steps * (G - 1)) / 1e9,
             "achieved_GBps": alg / secs / 1e9, "frac_of_hbm_peak": alg / secs / 1e9 / HBM_PEAK_GBPS,
+            "frac_of_measured_copy_rate": alg / secs / 1e9 / copy_gbps,
         }
     head = results[alphas[0]]
     if 1.0 in results:
@@ -262,6 +272,7 @@ def main() -> int:
                    "fill_every_step": fill},
         "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
         "by_alpha": {str(a): r for a, r in results.items()},
+        "stream_copy": {"GBps": copy_gbps, "what": "1 GiB device-to-device copy, read + written bytes per second (5 repeats)"},
         "roofline": roofline,
     }
     if schedules is not None:

@@ -73,6 +73,13 @@ def test_left_padded_batch_spans_attention_splits():
     _run(SMALL_BF16, 2, 650, 4, 0.9, 2, forced_seed=23, lengths=np.array([40, 650], np.int32))
 
 
+def test_bf16_shape_that_does_not_fit_the_matrix_core_tiles():
+    # d_model, d_ffn not multiples of 32, vocab not a multiple of 16: batched passes stay on the vector-ALU projections
+    shape = ModelShape("odd-bf16", L=3, d=264, H=4, H_kv=2, hd=64, F=696, V=1000, dtype="bf16")
+    _run(shape, 3, 21, 7, 0.8, 1, forced_seed=31)
+    _run(shape, 5, 40, 5, 0.8, 0, forced_seed=32, lengths=np.array([40, 7, 33, 1, 40], np.int32))
+
+
 def test_tiny_config_bf16_cache():
     _run(d3_inputs.TINY, 1, 16, 32, 0.97, 2, kv_dtype="bf16", forced_seed=5)
 

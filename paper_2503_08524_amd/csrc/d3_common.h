@@ -8,7 +8,7 @@ namespace d3 {
 
 constexpr int kWave = 64;          // CDNA wavefront
 constexpr int kMaxCols = 32;       // largest batch; columns of a decode pass
-constexpr int kPassCols = 64;      // columns of a prompt chunk on the matrix-core path (workspace buffers hold this many)
+constexpr int kPassCols = 128;     // columns of a prompt chunk on the matrix-core path (workspace buffers hold this many)
 constexpr int kMaxSplits = 32;     // context splits of one attention head
 constexpr size_t kGemmPartBytes = 16u << 20;   // partial accumulators of a K-sliced wide MFMA projection
 constexpr int kGemmPartTickets = 2048;         // row groups such a projection may have

@@ -1,5 +1,5 @@
-// Skinny GEMM on the matrix cores for 17..64 activation columns (large decode batches: up to 32; the chunked
-// prompt pass: up to 64): out[col][row] = sum_k W[row][k] * x[col][k], bf16 weights, activations x = hi + lo.
+// Skinny GEMM on the matrix cores for 17..128 activation columns (large decode batches: up to 32; the chunked
+// prompt pass: up to 128): out[col][row] = sum_k W[row][k] * x[col][k], bf16 weights, activations x = hi + lo.
 //
 // With 32 columns the activations of one 128-k turn are four 16 x 128 tiles (hi and lo of two column
 // tiles), twice the bytes of a weight tile pair: a kernel whose waves each fetch and re-shape their own
@@ -51,7 +51,8 @@ __device__ __forceinline__ void tile_to_frags(const TileRegs& r, char* tile, u32
 }
 
 // grid: (row groups of W * RT tiles, K slices).  CT column tiles (2: up to 32 columns, 4 waves per workgroup; 4: up to
-// 64 columns, 8 waves per workgroup, so that the bigger panel is shared by more row tiles).
+// 64 columns, 8 waves per workgroup, so that the bigger panel is shared by more row tiles; 8: up to 128 columns, 4 waves
+// with up to 512 registers each, the two panels fill the LDS).
 // A gate/up pair of tiles per wave wants 204 registers (two waves per SIMD); its launch has 2.7 workgroups per CU, so at that
 // size the last quarter of them starts only when the first ones have finished (entry times up to 24 us into a 42 us
 // launch).  Held to three waves per SIMD (168 registers, 33 spilled) every workgroup starts at once: 42 -> 38 us.
@@ -65,8 +66,8 @@ __global__ __launch_bounds__(W * 64, (MODE == MODE_SWIGLU && CT == 2) ? 3 : 1) v
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][kPanel] panels, then [W][kTile] staging tiles
     char (*panel)[kPanel] = reinterpret_cast<char (*)[kPanel]>(lds);
     char (*stage)[kTile] = reinterpret_cast<char (*)[kTile]>(lds + 2 * kPanel);
-    __shared__ float inv_rms[kPassCols];
-    __shared__ float ssq_w[W][kPassCols];
+    __shared__ float inv_rms[CT * 16];
+    __shared__ float ssq_w[W][CT * 16];
     __shared__ int is_last;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int K = a.K, nks = K / 32, turns = (nks + U - 1) / U;
@@ -367,6 +368,10 @@ int launch_one(const GemvArgs& a, int groups, int ks, hipStream_t s) {
 
 template <int MODE>
 int launch_rt(const GemvArgs& a, int ct, int rt, int groups, int ks, hipStream_t s) {
+    if (ct == 8) {
+        if constexpr (MODE != MODE_SWIGLU) { if (rt == 2) return launch_one<MODE, 2, 8, 4>(a, groups, ks, s); }
+        return launch_one<MODE, 1, 8, 4>(a, groups, ks, s);
+    }
     if (ct == 4) {
         if constexpr (MODE != MODE_SWIGLU) { if (rt == 2) return launch_one<MODE, 2, 4, 8>(a, groups, ks, s); }
         return launch_one<MODE, 1, 4, 8>(a, groups, ks, s);
@@ -389,17 +394,18 @@ int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, 
     // Measured at the 7B shape with 32 columns: one tile (pair) per wave beats two, and the launch is fastest when
     // its workgroups number about three per CU (what fits at once): K slices make up for the few row groups,
     // at least four turns each and at most eight of them (the publish / arrive / merge of the slices is not free).
-    const int ct = a.ncols > 32 ? 4 : 2;               // column tiles
+    const int ct = a.ncols > 64 ? 8 : a.ncols > 32 ? 4 : 2;   // column tiles
     const int w = ct == 4 ? 8 : 4;                     // waves per workgroup
     int rt = 1;
     // 64 columns, one stacked matrix (QKV, lm_head): two row tiles per wave share the panel fragments and put the whole
     // launch on the chip at once (7B QKV: 240 workgroups, 37.8 -> 30.9 us); the residual projections have too few row
     // tiles for that (down-projection: 128 workgroups, 32.6 -> 44 us)
     if (ct == 4 && mode == MODE_STORE) rt = 2;
-    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (v == 1 || mode != MODE_SWIGLU) rt = v;
+    if (ct == 8) rt = mode == MODE_STORE ? 2 : 1;
+    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (ct != 8 && (v == 1 || mode != MODE_SWIGLU)) rt = v;
     int groups = (tiles + w * rt - 1) / (w * rt);
     // up to 32 columns: three workgroups fit a CU; up to 64: one (its panels fill most of the LDS)
-    int ks = (ct == 4 ? 2 : 3) * n_cu / groups;
+    int ks = (ct == 8 ? 1 : ct == 4 ? 2 : 3) * n_cu / groups;
     if (ks > 8) ks = 8;
     if (const int v = env_int("D3_WIDE_KS", 1, 64)) ks = v;
     if (ks > turns / 4) ks = turns / 4;

@@ -96,12 +96,20 @@ def test_small_bf16_matrix_core_path(B, P):
 
 
 @pytest.mark.parametrize("shape,B,P", [(SMALL_BF16, 2, 24), (SMALL_BF16, 2, 97), (SMALL_BF16, 1, 81), (SMALL_GQA, 1, 80),
-                                       (SMALL_GQA, 2, 72), (SMALL_GQA, 1, 128)])
+                                       (SMALL_GQA, 2, 72), (SMALL_GQA, 1, 128), (SMALL_BF16, 2, 50), (SMALL_GQA, 1, 168),
+                                       (SMALL_GQA, 1, 136), (SMALL_BF16, 1, 144), (SMALL_GQA, 2, 145)])
 def test_prompt_lengths_that_end_in_every_chunk_width(shape, B, P):
-    # the prompt pass takes one sequence at a time in chunks of 64 columns; the last chunk has 24, 33, 17, 16, 8 or 64
-    # columns here, which ends in each of the projection kernels (packed, 16-column, 32-column and 64-column) and in both
-    # attention paths of a prompt chunk (per column on the vector ALUs at head_dim 64, query tiles on the matrix cores at 128)
+    # the prompt pass takes one sequence at a time in chunks of up to 128 columns; the chunks here have 24, 97, 81, 80, 72,
+    # 128, 50, 128 + 40, 128 + 8, 128 + 16 and 128 + 17 columns, which ends in each of the projection kernels (packed,
+    # 16-column, and the panel kernel with two, four and eight column tiles) and in both attention paths of a prompt chunk
+    # (per column on the vector ALUs at head_dim 64, query tiles on the matrix cores at 128)
     _run(shape, B, P, 4, 0.8, 1, forced_seed=9)
+
+
+def test_prompt_chunks_of_64_columns(monkeypatch):
+    # the width the large shapes use (more row groups than compute units), forced here on a small one
+    monkeypatch.setenv("D3_PREFILL_COLS", "64")
+    _run(SMALL_GQA, 2, 150, 4, 0.8, 1, forced_seed=9)
 
 
 @pytest.mark.parametrize("B,kv", [(1, "f16"), (3, "f16"), (2, "bf16"), (2, "f32")])

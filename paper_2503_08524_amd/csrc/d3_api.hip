@@ -575,12 +575,11 @@ int prefill_impl(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32
         // one sequence at a time, 32 consecutive positions per pass: the attention of such a chunk reads every cache
         // row once per tile of queries instead of once per query
         // the matrix-core path takes 128 columns a pass (the weights are streamed once per pass); D3_PREFILL_COLS=64 halves that
-        // 128 columns run one 4-wave workgroup per CU; a gate/up matrix with more groups of 4 row-tile pairs than CUs would
-        // take several rounds of them and does better at 64 (70B shape: 4.24 s against 4.12 s; 7B: 4.75 against 5.33)
+        // (projections of large matrices split such a pass into two launches of 64 columns by themselves)
         const char* cols_env = getenv("D3_PREFILL_COLS");                 // read per call: tests switch it
         const int cols_v = cols_env ? atoi(cols_env) : 0;
         const int forced_cols = cols_v == 64 || cols_v == 128 ? cols_v : 0;
-        const int wide_cols = forced_cols ? forced_cols : (d.d_ffn / 64 <= ctx->n_cu ? kPassCols : 64);
+        const int wide_cols = forced_cols ? forced_cols : kPassCols;
         const int chunk_cols = ctx->mfma_ok && gemm_mfma_wide_enabled() ? wide_cols : kMaxCols;
         for (int b = 0; b < B; ++b) {
             for (int base = pos_begin == 0 ? ctx->row0[b] : 0; base < P;) {     // padding columns are not computed

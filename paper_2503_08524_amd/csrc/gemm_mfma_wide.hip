@@ -387,14 +387,51 @@ int launch_rt(const GemvArgs& a, int ct, int rt, int groups, int ks, hipStream_t
 
 // Requirements: those of launch_gemm_mfma, 17 <= ncols <= kPassCols (x_hi / x_lo hold kPassCols rows); a.part holds kGemmPartBytes and a.part_tickets
 // kGemmPartTickets zeroed counters (the kernel leaves them zero).
+namespace {
+
+int launch_config(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups, int force_ct);
+
+// Column halves of a pass of more than 64 columns, both with the 64-column kernel (the same row groups, so the partial
+// sums of squares of all columns have one layout).
+int launch_halves(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
+    GemvArgs lo = a;
+    lo.ncols = 64;
+    int rc = launch_config(lo, mode, n_cu, s, n_groups, 4);
+    if (rc != 0) return rc;
+    GemvArgs hi = a;
+    hi.ncols = a.ncols - 64;
+    hi.x_hi += (size_t)64 * a.x_stride; hi.x_lo += (size_t)64 * a.x_stride;
+    if (hi.out) hi.out += (size_t)64 * a.out_stride;
+    if (hi.out_hi) { hi.out_hi += (size_t)64 * a.out_stride; hi.out_lo += (size_t)64 * a.out_stride; }
+    if (hi.ssq_in) hi.ssq_in += (size_t)64 * kSsqStride;
+    if (hi.ssq_out) hi.ssq_out += (size_t)64 * kSsqStride;
+    return launch_config(hi, mode, n_cu, s, nullptr, 4);
+}
+
+}  // namespace
+
 int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
+    // More than 64 columns: one launch of the 128-column kernel (four waves per workgroup) when the matrix is small enough
+    // for its fixed costs to matter, else two of the 64-column kernel, whose eight-wave workgroups stream a large matrix
+    // faster (70B shape, per 128 columns: gate/up 940 MB 396 against 330 us, down 470 MB 252 against 224 us; QKV 168 MB 85
+    // against 95 us, O 134 MB 84 against 100 us)
+    const size_t weight_bytes = (size_t)a.total_rows * a.K * 2 * (mode == MODE_SWIGLU ? 2 : 1);
+    size_t split_mb = 300;
+    if (const char* e = getenv("D3_WIDE_SPLIT_MB")) { const long v = atol(e); if (v >= 0 && v <= (1 << 20)) split_mb = (size_t)v; }   // read per call: tests switch it
+    if (a.ncols > 64 && weight_bytes > (split_mb << 20)) return launch_halves(a, mode, n_cu, s, n_groups);
+    return launch_config(a, mode, n_cu, s, n_groups, 0);
+}
+
+namespace {
+
+int launch_config(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups, int force_ct) {
     const int tiles = a.total_rows / 16;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;
     // Measured at the 7B shape with 32 columns: one tile (pair) per wave beats two, and the launch is fastest when
     // its workgroups number about three per CU (what fits at once): K slices make up for the few row groups,
     // at least four turns each and at most eight of them (the publish / arrive / merge of the slices is not free).
-    const int ct = a.ncols > 64 ? 8 : a.ncols > 32 ? 4 : 2;   // column tiles
+    const int ct = force_ct ? force_ct : a.ncols > 64 ? 8 : a.ncols > 32 ? 4 : 2;   // column tiles
     const int w = ct == 4 ? 8 : 4;                     // waves per workgroup
     int rt = 1;
     // 64 columns, one stacked matrix (QKV, lm_head): two row tiles per wave share the panel fragments and put the whole
@@ -418,5 +455,7 @@ int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, 
     if (mode == MODE_RESID) return launch_rt<MODE_RESID>(a, ct, rt, groups, ks, s);
     return launch_rt<MODE_SWIGLU>(a, ct, rt, groups, ks, s);
 }
+
+}  // namespace
 
 }  // namespace d3

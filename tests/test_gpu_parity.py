@@ -106,6 +106,13 @@ def test_prompt_lengths_that_end_in_every_chunk_width(shape, B, P):
     _run(shape, B, P, 4, 0.8, 1, forced_seed=9)
 
 
+def test_wide_prompt_chunks_as_two_launches_of_64_columns(monkeypatch):
+    # what the projections of large matrices (hundreds of MB) do with a chunk of more than 64 columns, forced on small ones
+    monkeypatch.setenv("D3_WIDE_SPLIT_MB", "0")
+    _run(SMALL_GQA, 2, 150, 4, 0.8, 1, forced_seed=9)
+    _run(SMALL_BF16, 1, 97, 4, 0.8, 1, forced_seed=9)
+
+
 def test_prompt_chunks_of_64_columns(monkeypatch):
     # the width the large shapes use (more row groups than compute units), forced here on a small one
     monkeypatch.setenv("D3_PREFILL_COLS", "64")

@@ -295,13 +295,14 @@ def test_recompute_fill_call_rules():
     dec.close()
 
 
-def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split():
+@pytest.mark.parametrize("P2", [10, 150])
+def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split(P2):
     """A second prompt that starts at row 125: its chunk's query tiles (4 queries x 4 heads of a KV head at this shape) are
     not aligned with the context splits (multiples of 64 rows, 128 by default), so some queries of a tile have no row in
     the last split while others do."""
     shape = ModelShape("small-gqa", L=3, d=512, H=8, H_kv=2, hd=128, F=1376, V=2000, dtype="bf16")
     B, P, G, alpha, start = 2, 114, 12, 0.9, 1
-    P2, G2 = 10, 3
+    G2 = 3                                             # P2 = 150: a full 128-column chunk and a remainder, both on a cache that already holds rows
     w = d3_inputs.make_weights(shape, 3)
     prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
     forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)

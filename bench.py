@@ -249,12 +249,17 @@ def main() -> int:
     # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
     # each scaled by what a plain 1 GiB copy reads on the same counter); only known for the profiled workload
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "decode_7b_b1_hbm_traffic.json")
-    if args.config == "7b" and kclass == binding.D3_K_GATE_UP and os.path.exists(tpath):
-        with open(tpath) as f:
-            ks = [v for name, v in json.load(f)["kernels"].items() if "gemv_alu_kernel<unsigned short, 1, 2, true>" in name]
-        if ks:
-            traffic = ks[0]["fetch_bytes_per_launch"] + ks[0]["write_bytes_per_launch"]
+    profiled = {"7b": ("decode_7b_b1", "gemv_alu_kernel<unsigned short, 1, 2, true>"),       # gate/up kernel of each configuration
+                "13b": ("decode_13b_b4", "gemm_mfma_kernel<1, 2, 2, true>"),
+                "70b": ("decode_70b_b8", "gemm_mfma_kernel<1, 2, 1, true>")}
+    if args.config in profiled and kclass == binding.D3_K_GATE_UP:
+        stem, kname = profiled[args.config]
+        tpath = os.path.join(ROOT, "profiles", stem + "_hbm_traffic.json")
+        if os.path.exists(tpath):
+            with open(tpath) as f:
+                ks = [v for name, v in json.load(f)["kernels"].items() if kname in name]
+            if ks and ks[0]["write_bytes_per_launch"] is not None:
+                traffic = ks[0]["fetch_bytes_per_launch"] + ks[0]["write_bytes_per_launch"]
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                 "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": bytes_per_launch}

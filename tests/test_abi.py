@@ -65,6 +65,19 @@ def test_plan_table_rejects_steps_that_do_not_fit(lib):
         d3.d3_plan_depth_linear(8, 9, 2, 0, 4)
 
 
+def test_plan_from_table_lists_exactly_the_blocks_outside_each_window(lib):
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        L = int(rng.integers(1, 90))
+        n = int(rng.integers(1, 40))
+        keep = rng.integers(0, L + 1, size=n)
+        drop = np.array([int(rng.integers(0, k + 1)) for k in keep])       # window [drop, drop + L - keep) ends at or before L
+        ids = d3.d3_plan_from_table(L, keep, drop)
+        for i in range(n):
+            want = [l for l in range(L) if not (drop[i] <= l < drop[i] + L - keep[i])]
+            assert ids[i, : keep[i]].tolist() == want and (ids[i, keep[i]:] == -1).all()
+
+
 def test_plan_accepts_null_outputs_and_zero_steps(lib):
     assert lib.d3_plan_depth(8, 0.9, 3, 0, 5, None, None, None) == 0
     assert lib.d3_plan_depth(8, 0.9, 3, 0, 0, None, None, None) == 0

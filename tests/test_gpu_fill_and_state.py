@@ -211,6 +211,59 @@ def test_recompute_fill_matches_oracle_and_continuation_reads_it(B, start, kv):
 
 
 @pytest.mark.parametrize("mode", ["copy", "recompute"])
+def test_schedule_whose_depth_rises_again_reads_the_filled_rows(mode):
+    """The case the paper's first challenge describes (Section 1): a token runs blocks that an earlier token skipped, so
+    the earlier token's missing K/V rows are read within the same request.  A caller-made schedule (not nested, windows
+    at different places) with the fill after every step, against the oracle stepped the same way."""
+    import torch
+    from paper_2503_08524_amd import binding
+    shape, B, P = SHAPE, 2, 7
+    L = shape.L
+    keep = np.array([6, 3, 5, 2, 6, 4, 1, 6, 0, 5], np.int32)
+    drop = np.array([0, 1, 0, 2, 0, 4, 1, 0, 0, 5], np.int32)
+    G = len(keep)
+    w = d3_inputs.make_weights(shape, 2)
+    prompts = d3_inputs.make_prompt(B, P, shape.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, shape.V, seed=4)
+    fm = binding.D3_FILL_RECOMPUTE if mode == "recompute" else binding.D3_FILL_COPY
+    print(f"case rising depth, fill {mode}", flush=True)
+    dec = binding.Decoder(shape, binding.weights_to_device(shape, w), B, P + G, kv_dtype="f16")
+    dec.set_plan_table(keep, drop)
+    dec.set_fill_mode(fm)
+    dev = "cuda:0"
+    logits = torch.zeros(B, shape.V, device=dev)
+    cur = dec.prefill(torch.from_numpy(prompts).to(dev), logits=logits)
+    got = [logits.cpu().numpy().copy()]
+    nxt = torch.zeros_like(cur)
+    for i in range(1, G):
+        cur = torch.from_numpy(np.ascontiguousarray(forced[:, i - 1], np.int32)).to(dev)
+        dec.decode_step(cur, i, nxt, logits=logits)
+        dec.fill_missing_kv(dec.n_ctx - 1, dec.n_ctx, fm)
+        got.append(logits.cpu().numpy().copy())
+    dec.sync_check()
+    ids = binding.d3_plan_from_table(L, keep, drop)
+    oracle.set_threads(helpers.oracle_threads())
+    model = oracle.OracleModel(shape, w)
+    worst = 0.0
+    for b in range(B):
+        seq = model.new_seq(P + G)
+        for t in range(P):
+            _, lg = seq.forward_token(int(prompts[b, t]), t, list(range(L)), False, t == P - 1)
+        worst = max(worst, float(np.abs(got[0][b] - lg).max()))
+        for i in range(1, G):
+            blocks = ids[i, : keep[i]]
+            hid, lg = seq.forward_token(int(forced[b, i - 1]), P + i - 1, blocks, True, True)
+            if mode == "copy":
+                seq.fill_missing_kv(P + i - 1, int(drop[i]), int(L - keep[i]))
+            else:
+                seq.fill_recompute(P + i - 1, int(drop[i]), int(L - keep[i]), hid[int((blocks < drop[i]).sum())])
+            worst = max(worst, float(np.abs(got[i][b] - lg).max()))
+    print(f"  worst logit abs err {worst:.3e}", flush=True)
+    assert worst <= helpers.LOGIT_ATOL
+    dec.close()
+
+
+@pytest.mark.parametrize("mode", ["copy", "recompute"])
 def test_left_padded_batch_fill_and_continuation(mode):
     """A ragged batch: the fill of each sequence's dropped blocks and a second request on the same cache (equal tails)
     against per-sequence oracles that know nothing of the padding."""

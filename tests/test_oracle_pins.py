@@ -321,3 +321,38 @@ def test_oracle_follows_a_linear_plan_like_the_no_cache_brute_force(start):
         np.testing.assert_allclose(gen.logits[i], logits[i], rtol=0, atol=1e-11)
         np.testing.assert_allclose(gen.hidden[i], hidden[i], rtol=0, atol=1e-11)
     assert [h.shape[0] - 1 for h in gen.hidden] == plan[0][:G].tolist()
+
+
+@pytest.mark.parametrize("mode", ["copy", "recompute"])
+def test_rising_depth_with_fill_every_step_matches_brute_force(mode):
+    # Section 1, first challenge: a token runs blocks that an earlier token skipped and reads that token's filled rows
+    # inside the same request.  The oracle, stepped with a caller-made schedule and the fill after every step, against the
+    # no-cache brute force in which a skipped row exposes its source block's K/V (copy) or the K/V of its copied hidden
+    # state (recompute).
+    shape = MICRO
+    L = shape.L
+    w, w64, model = _setup(shape, seed=11)
+    P = 4
+    keep = [5, 2, 4, 1, 5, 3, 5]
+    drop = [0, 1, 1, 1, 0, 2, 0]
+    prompt = d3_inputs.make_prompt(1, P, shape.V, seed=6)[0]
+    fed = d3_inputs.make_prompt(1, len(keep) - 1, shape.V, seed=8)[0]
+    seq = model.new_seq(P + len(keep))
+    for t in range(P):
+        seq.forward_token(int(prompt[t]), t, list(range(L)))
+    tokens = [int(t) for t in prompt]
+    row_blocks = [list(range(L))] * P
+    row_src = [None] * P
+    for i in range(1, len(keep)):
+        n = L - keep[i]
+        blocks = [l for l in range(L) if not (drop[i] <= l < drop[i] + n)]
+        hid, logits = seq.forward_token(int(fed[i - 1]), P + i - 1, blocks, True, True)
+        tokens.append(int(fed[i - 1]))
+        row_blocks.append(blocks)
+        row_src.append(drop[i] - 1 if n else None)
+        want, _ = bruteforce.forward_all(shape, w64, tokens, row_blocks, fill=True if mode == "copy" else "recompute", row_src=row_src)
+        np.testing.assert_allclose(logits, want, rtol=0, atol=1e-11)
+        if mode == "copy":
+            seq.fill_missing_kv(P + i - 1, drop[i], n)
+        else:
+            seq.fill_recompute(P + i - 1, drop[i], n, hid[sum(1 for l in blocks if l < drop[i])])

@@ -104,7 +104,7 @@ struct d3_ctx {
     int n_cu;
     int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
     bool prefill_by_seq;          // prompt pass one sequence at a time (D3_PREFILL_BY_SEQ, default on)
-    int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU, default 2)
+    int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU; default 2, 1 for grouped-query models)
     int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
@@ -183,7 +183,10 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->n_cu = prop.multiProcessorCount;
     c->gemv_wgs_per_cu = 3;
     c->gemv_head_start = 0;
-    c->attn_wgs_per_cu = 2;
+    // grouped-query models on the MFMA attention kernel (fp16 cache, head_dim 128, 4 or 8 heads per KV head) do better with
+    // one workgroup per CU (70B shape, batch 8: 24.41 against 24.55 ms a step), the others with two (13B, batch 4: 5.71 against 5.78)
+    c->attn_wgs_per_cu = (desc->kv_dtype == D3_F16 && desc->head_dim == 128 && desc->n_kv_heads > 0 &&
+                          (desc->n_heads / desc->n_kv_heads == 4 || desc->n_heads / desc->n_kv_heads == 8)) ? 1 : 2;
     c->prefill_by_seq = true;
     if (const char* env = getenv("D3_PREFILL_BY_SEQ")) c->prefill_by_seq = atoi(env) != 0;
     if (const char* env = getenv("D3_ATTN_WGS_PER_CU")) { const int v = atoi(env); if (v >= 1 && v <= 16) c->attn_wgs_per_cu = v; }

@@ -90,7 +90,7 @@ def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy",
             if fill != "none":
                 dec.fill_missing_kv(P + i - 1, P + i, FILL_MODES[fill])
             cur, nxt = nxt, cur
-    dec.sync_check()
+    dec.synchronize()
     return time.perf_counter() - t0
 
 
@@ -227,12 +227,7 @@ def main() -> int:
 
     # dominant kernel, every launch bracketed by HIP events on the launch stream, over one more full-depth request
     wbytes = 4 if shape.dtype == "f32" else 2
-    if dec.persistent_workgroups > 0:
-        # the persistent decode step: one launch = one token; its algorithmic bytes are the step's
-        keep1, _, _ = binding.d3_plan_depth(shape.L, 1.0, start, 0, G)
-        kernel = "persistent decode step (all %d blocks + lm_head + argmax in one launch)" % shape.L
-        kclass, bytes_per_launch = binding.D3_K_STEP, algorithmic_bytes(shape, B, P, G, keep1, kv_bytes) / (G - 1)
-    elif args.config == "7b-b32":
+    if args.config == "7b-b32":
         # at batch 32 the cache rows outweigh the weights: attention is the dominant kernel (one launch per block;
         # bytes averaged over the request's steps: K and V rows of B sequences, read once)
         kernel = "decode attention (RoPE + KV append + split merge included)"
@@ -273,7 +268,6 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{shape.name} B={B} P={P if not lengths else list(lengths)} G={G} alpha={alphas[0]} start_layer={start}",
                    "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
-                   "persistent_step_workgroups": dec.persistent_workgroups,
                    "fill_every_step": fill},
         "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
         "by_alpha": {str(a): r for a, r in results.items()},

@@ -19,7 +19,7 @@
  *     therefore the executed blocks (Section 1, challenge (ii); Table 1).
  *   - Layouts: linear weights row-major [out][in], float32 or bf16; RMSNorm
  *     gains float32; KV cache [L][max_batch][H_kv][max_seq][head_dim] for K and
- *     for V (keys stored after the rotary embedding), float32, bf16 or fp16.
+ *     for V (keys stored after the rotary embedding), float32 or fp16.
  */
 #ifndef D3_H
 #define D3_H
@@ -45,7 +45,11 @@ typedef struct {
     int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
     float rms_eps, rope_base;
     int32_t weight_dtype; /* D3_F32 or D3_BF16: every linear weight and the embedding table */
-    int32_t kv_dtype;     /* D3_F32, D3_BF16 or D3_F16 (IEEE half, values clamped to +-65504): the KV cache */
+    int32_t kv_dtype;     /* the KV cache: D3_F16 (IEEE half, values clamped to +-65504) or D3_F32.  The rounding of
+                           * the cache rows is what separates the result from full precision: about 4.5e-4 of the
+                           * hidden state's norm per block with D3_F16, growing like sqrt(blocks run), against
+                           * 5e-6 with D3_F32; models of more than about 48 blocks need D3_F32 to keep logits within
+                           * 2e-2.  D3_BF16 (3.7e-3 per block) is refused. */
     int32_t max_batch, max_seq;
 } d3_model_desc;
 
@@ -84,7 +88,7 @@ int d3_plan_depth(int32_t L, double alpha, int32_t start_layer, int32_t min_keep
 
 /* Linear decay between two bounds, the schedule of the batched comparison
  * method that Section 3.4 contrasts with the power law (Section 4.1 runs it
- * "within upper and lower bounds of the executable layers"; its constants are
+ * between an upper and a lower bound on the executed blocks; its constants are
  * not in the paper, so the bounds are arguments).  In integers, for i in
  * [0, n_steps):  keep[i] = keep_first - ceil((keep_first - keep_last) * i /
  * max(1, n_steps - 1)), i.e. floor of the straight line from keep_first at
@@ -118,9 +122,9 @@ int d3_create(d3_ctx **out, const d3_model_desc *desc, const d3_weights *weights
               void *v_cache, void *workspace, size_t workspace_bytes);
 int d3_destroy(d3_ctx *ctx);
 
-/* Start a request's schedule: computes the plan with d3_plan_depth and uploads
- * the layer-index table (n_steps <= 4096).  The next d3_decode_step must be
- * step 1.  Keeps the cache contents and row count. */
+/* Start a request's schedule: computes the plan with d3_plan_depth and keeps
+ * the layer-index table (n_steps <= 4096; host only, no device work).  The next
+ * d3_decode_step must be step 1.  Keeps the cache contents and row count. */
 int d3_set_plan(d3_ctx *ctx, double alpha, int32_t start_layer, int32_t min_keep, int32_t n_steps);
 
 /* Same, for a schedule the caller made (d3_plan_depth_linear, or any table
@@ -186,8 +190,7 @@ int d3_fill_missing_kv(d3_ctx *ctx, int32_t pos_begin, int32_t pos_end, int32_t 
 
 /* Which fill the caller will use.  With D3_FILL_RECOMPUTE every decode step keeps the
  * residual that enters its drop window (one device copy of [B][d_model] floats per
- * step) for the d3_fill_missing_kv call that follows it.  Default D3_FILL_COPY.
- * D3_ESTATE with the persistent decode step. */
+ * step) for the d3_fill_missing_kv call that follows it.  Default D3_FILL_COPY. */
 int d3_set_fill_mode(d3_ctx *ctx, int32_t mode);
 
 /* Current number of cache rows per sequence. */
@@ -201,35 +204,17 @@ int32_t d3_n_ctx(const d3_ctx *ctx);
 int d3_truncate(d3_ctx *ctx, int32_t n_rows);
 
 /* Measurement aid: per-launch timing of one kernel class with HIP events recorded
- * on the caller's stream (the projections dominate the step: "computational cost
- * scales linearly with the number of decoder blocks", Section 1).  While a class is
+ * on the caller's stream (the projections dominate the step: its cost is that of
+ * the decoder blocks it runs, Section 1).  While a class is
  * selected, every launch of it is bracketed by two events (at most 16384 launches
  * are recorded; further ones run untimed).  d3_profile_read synchronises on the
  * recorded events, returns their summed duration and count, and clears them.
  * Selecting D3_K_NONE switches the bracketing off. */
 typedef enum {
-    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6,
-    D3_K_STEP = 7 /* the persistent one-launch decode step (batch 1) */
+    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6
 } d3_kernel_class;
 int d3_profile_select(d3_ctx *ctx, int32_t kernel_class);
 int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
-
-/* With the environment variable D3_PERSISTENT=1 at d3_create, batch-1 decode steps of bf16 models
- * with head_dim 128 run as ONE persistent cooperative
- * launch per step whose phases are separated by software grid barriers (Section 3.4: the step's
- * cost is the kept blocks' weights, so launch overheads between projections are what is left to
- * remove).  Every barrier wait is bounded; if one ever expires the step's outputs are invalid.
- * d3_sync_check synchronises the stream and reports that case as D3_EDEVICE (and re-arms the
- * barrier); D3_OK otherwise.  d3_uses_persistent_step returns the launch's workgroup count, or 0
- * when the context decodes with one launch per projection (the default). */
-int d3_sync_check(d3_ctx *ctx, void *hip_stream);
-int d3_uses_persistent_step(const d3_ctx *ctx);
-
-/* Debug aid for the persistent step: device_buffer (dev, uint64 [workgroups][10 * n_layers], or NULL to
- * switch off) receives every workgroup's 100 MHz timestamps at the phase boundaries of the next steps:
- * per kept block 10 marks (start / done of the QKV projection, of attention, and of the O, gate-up and
- * down projections). */
-int d3_debug_timeline(d3_ctx *ctx, void *device_buffer);
 
 #ifdef __cplusplus
 }

@@ -13,15 +13,6 @@ template <> struct KvVec<float> {
     static __device__ __forceinline__ float round(float v) { return v; }
     static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
 };
-template <> struct KvVec<bf16_t> {
-    static constexpr int N = 8;
-    static __device__ __forceinline__ void unpack(const uint4& v, float (&f)[8]) {
-        f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
-        f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
-    }
-    static __device__ __forceinline__ float round(float v) { return bf16_to_f32(f32_to_bf16(v)); }
-    static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
-};
 template <> struct KvVec<f16_t> {
     static constexpr int N = 8;
     typedef _Float16 half8 __attribute__((ext_vector_type(8)));

@@ -35,17 +35,11 @@ __global__ __launch_bounds__(256) void attn_qtile_kernel(AttnArgs a) {
     attn_qtile_mfma<4, GH>(a, blockIdx.x, blockIdx.y * GH, blockIdx.z * (16 / GH), sh);
 }
 
-// D3_ATTN_MFMA=0 keeps grouped-query attention on the vector ALUs (for comparisons)
-bool attn_mfma_enabled() {
-    static const bool on = [] { const char* e = getenv("D3_ATTN_MFMA"); return !(e && e[0] == '0'); }();
-    return on;
-}
-
 template <typename T, int HD, bool ROPE>
-int launch_g(const AttnArgs& a, hipStream_t s) {
+int launch_g(const AttnArgs& a, bool use_mfma, hipStream_t s) {
     const int group = a.H / a.H_kv;
     if constexpr (std::is_same<T, f16_t>::value && HD == 128 && !ROPE) {
-        if (a.qtile && (group == 1 || group == 2 || group == 4 || group == 8) && attn_mfma_enabled()) {
+        if (a.qtile && (group == 1 || group == 2 || group == 4 || group == 8) && use_mfma) {
             const int qt = 16 / group;
             dim3 grid(a.n_splits, a.H / group, (a.ncols + qt - 1) / qt);
             if (group == 8) hipLaunchKernelGGL((attn_qtile_kernel<8>), grid, dim3(256), 0, s, a);
@@ -56,7 +50,7 @@ int launch_g(const AttnArgs& a, hipStream_t s) {
         }
     }
     if constexpr (std::is_same<T, f16_t>::value && HD == 128) {
-        if ((group == 4 || group == 8) && attn_mfma_enabled()) {
+        if ((group == 4 || group == 8) && use_mfma) {
             dim3 grid(a.n_splits, a.H / group, a.ncols);
             if (group == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, ROPE>), grid, dim3(256), 0, s, a);
             else hipLaunchKernelGGL((attn_mfma_kernel<4, ROPE>), grid, dim3(256), 0, s, a);
@@ -77,16 +71,17 @@ int launch_g(const AttnArgs& a, hipStream_t s) {
 // Requirements (checked by the caller): hd in {64, 128}; split_len * n_splits >= longest context;
 // n_splits <= kMaxSplits; tickets zero on entry (the kernel leaves them zero).
 template <bool ROPE>
-int launch_t(const AttnArgs& a, int kv_dtype, hipStream_t s) {
-    if (kv_dtype == 0) return a.hd == 64 ? launch_g<float, 64, ROPE>(a, s) : launch_g<float, 128, ROPE>(a, s);
-    if (kv_dtype == 1) return a.hd == 64 ? launch_g<bf16_t, 64, ROPE>(a, s) : launch_g<bf16_t, 128, ROPE>(a, s);
-    return a.hd == 64 ? launch_g<f16_t, 64, ROPE>(a, s) : launch_g<f16_t, 128, ROPE>(a, s);
+int launch_t(const AttnArgs& a, int kv_dtype, bool use_mfma, hipStream_t s) {
+    if (kv_dtype == 0) return a.hd == 64 ? launch_g<float, 64, ROPE>(a, use_mfma, s) : launch_g<float, 128, ROPE>(a, use_mfma, s);
+    if (kv_dtype == 2) return a.hd == 64 ? launch_g<f16_t, 64, ROPE>(a, use_mfma, s) : launch_g<f16_t, 128, ROPE>(a, use_mfma, s);
+    return (int)hipErrorInvalidValue;
 }
 
 // With rope_cs set, q and the newest K/V row of each column are still unrotated in the projection buffer and
 // the kernel rotates and appends them itself; the columns of such a pass must belong to different sequences.
-int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s) {
-    return a.rope_cs ? launch_t<true>(a, kv_dtype, s) : launch_t<false>(a, kv_dtype, s);
+// use_mfma = false keeps grouped-query and query-tile attention on the vector ALUs (for comparisons).
+int launch_attention(const AttnArgs& a, int kv_dtype, bool use_mfma, hipStream_t s) {
+    return a.rope_cs ? launch_t<true>(a, kv_dtype, use_mfma, s) : launch_t<false>(a, kv_dtype, use_mfma, s);
 }
 
 }  // namespace d3

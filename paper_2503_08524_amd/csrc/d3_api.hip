@@ -9,7 +9,6 @@
 
 #include "../../include/d3.h"
 #include "d3_common.h"
-#include "decode_mega.h"
 #include "d3_error.h"
 
 using namespace d3;
@@ -22,7 +21,7 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {          // byte offsets into the workspace
-    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, layer_table, layer_ptrs, barrier, cand_val, cand_idx, n_hi, n_lo, ssq, h_skip, gemm_part, gemm_tickets, row0, total;
+    size_t x, qkv, attn_o, act, part_o, part_ml, tickets, logits, s_hi, s_lo, f_hi, f_lo, inv_freq, rope_cs, n_hi, n_lo, ssq, h_skip, gemm_part, gemm_tickets, row0, total;
 };
 
 // The vector-ALU GEMV stages one column of its input in LDS.
@@ -48,8 +47,10 @@ int check_desc(const d3_model_desc* d) {
     if (d->max_batch < 1 || d->max_batch > kMaxCols) return fail(D3_ESHAPE, "max_batch must be in [1, %d] (got %d)", kMaxCols, d->max_batch);
     if (d->max_seq < 1 || d->max_seq > kMaxSplits * 8192) return fail(D3_ESHAPE, "max_seq must be in [1, %d]", kMaxSplits * 8192);
     if (d->weight_dtype != D3_F32 && d->weight_dtype != D3_BF16) return fail(D3_EINVAL, "weight_dtype must be D3_F32 or D3_BF16");
-    if (d->kv_dtype != D3_F32 && d->kv_dtype != D3_BF16 && d->kv_dtype != D3_F16)
-        return fail(D3_EINVAL, "kv_dtype must be D3_F32, D3_BF16 or D3_F16");
+    if (d->kv_dtype == D3_BF16)
+        return fail(D3_EINVAL, "kv_dtype D3_BF16 is not offered: a cache with an 8-bit mantissa puts the hidden state 3.7e-3 (relative) off per "
+                               "block at real widths, outside the logit tolerance after two blocks; use D3_F16 (same bytes) or D3_F32");
+    if (d->kv_dtype != D3_F32 && d->kv_dtype != D3_F16) return fail(D3_EINVAL, "kv_dtype must be D3_F32 or D3_F16");
     if (!(d->rms_eps >= 0.f) || !(d->rope_base > 1.f)) return fail(D3_EINVAL, "rms_eps must be >= 0 and rope_base > 1");
     if (!alu_fits(*d) && !mfma_fits(*d))
         return fail(D3_ESHAPE, "d_model / d_ffn fit neither the LDS-staged GEMV nor the matrix-core path");
@@ -77,9 +78,6 @@ Layout make_layout(const d3_model_desc& d) {
     l.f_lo = take(C * (size_t)d.d_ffn * 2);
     l.inv_freq = take((size_t)d.head_dim / 2 * 8);
     l.rope_cs = take(C * (size_t)d.head_dim / 2 * 8);
-    l.layer_table = take((size_t)kMaxPlanSteps * d.n_layers * 4);
-    l.layer_ptrs = take((size_t)d.n_layers * sizeof(d3_layer_weights));
-    l.barrier = take(512 * 4);
     l.n_hi = take(C * d.d_model * 2);
     l.n_lo = take(C * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
@@ -87,13 +85,37 @@ Layout make_layout(const d3_model_desc& d) {
     l.gemm_part = take(kGemmPartBytes);
     l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
     l.row0 = take(kPassCols * 4);
-    l.cand_val = take(4096 * 4);
-    l.cand_idx = take(4096 * 4);
     l.total = o;
     return l;
 }
 
 }  // namespace
+
+namespace {
+int env_int(const char* name, long lo, long hi, long dflt) {
+    const char* e = getenv(name);
+    if (!e) return (int)dflt;
+    const long v = atol(e);
+    return (int)(v >= lo && v <= hi ? v : dflt);
+}
+}  // namespace
+
+namespace d3 {
+Tuning tuning_from_env() {
+    Tuning t;
+    t.mfma_rt = env_int("D3_MFMA_RT", 1, 4, 0);
+    t.mfma_waves = env_int("D3_MFMA_WAVES", 1, 8, 0);
+    t.mfma_wide = env_int("D3_MFMA_WIDE", 0, 1, 1) != 0;
+    t.wide_rt = env_int("D3_WIDE_RT", 1, 2, 0);
+    t.wide_ks = env_int("D3_WIDE_KS", 1, 64, 0);
+    t.wide_split_mb = (size_t)env_int("D3_WIDE_SPLIT_MB", 0, 1 << 20, 300);
+    t.attn_mfma = env_int("D3_ATTN_MFMA", 0, 1, 1) != 0;
+    t.attn_min_split = env_int("D3_ATTN_MIN_SPLIT", 64, 65536, 128) / 64 * 64;
+    const int pc = env_int("D3_PREFILL_COLS", 64, 128, 0);
+    t.prefill_cols = pc == 64 || pc == 128 ? pc : 0;
+    return t;
+}
+}  // namespace d3
 
 struct d3_ctx {
     d3_model_desc desc;
@@ -102,7 +124,7 @@ struct d3_ctx {
     char *k_cache, *v_cache, *ws;
     Layout lay;
     int n_cu;
-    int gemv_head_start;          // D3_GEMV_HEAD_START: see GemvArgs::head_start
+    Tuning tn;                    // launch-shape overrides, read from the environment once by d3_create
     bool prefill_by_seq;          // prompt pass one sequence at a time (D3_PREFILL_BY_SEQ, default on)
     int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU; default 2, 1 for grouped-query models)
     int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
@@ -120,12 +142,6 @@ struct d3_ctx {
     int fill_mode;                // D3_FILL_RECOMPUTE: decode steps keep the residual that enters their drop window
     int skip_row;                 // cache row whose residual h_skip holds (-1: none)
 
-    // persistent one-launch decode step (batch 1, bf16 weights, head_dim 128)
-    bool mega_ok;
-    int mega_wgs;                 // workgroups of the cooperative launch
-    int mega_depth;               // weight-load steps in flight per wave (D3_PERSISTENT_DEPTH: 8 or 12)
-    unsigned bar_epoch;           // grid barriers completed so far
-    unsigned long long* debug_ts; // optional device buffer for the persistent step's phase timeline
     // per-launch timing of one kernel class
     int prof_class;
     std::vector<hipEvent_t> prof_events;   // pairs (start, stop), created on first use
@@ -182,19 +198,14 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
     c->gemv_wgs_per_cu = 3;
-    c->gemv_head_start = 0;
+    c->tn = tuning_from_env();
     // grouped-query models on the MFMA attention kernel (fp16 cache, head_dim 128, 4 or 8 heads per KV head) do better with
     // one workgroup per CU (70B shape, batch 8: 24.41 against 24.55 ms a step), the others with two (13B, batch 4: 5.71 against 5.78)
     c->attn_wgs_per_cu = (desc->kv_dtype == D3_F16 && desc->head_dim == 128 && desc->n_kv_heads > 0 &&
                           (desc->n_heads / desc->n_kv_heads == 4 || desc->n_heads / desc->n_kv_heads == 8)) ? 1 : 2;
-    c->prefill_by_seq = true;
-    if (const char* env = getenv("D3_PREFILL_BY_SEQ")) c->prefill_by_seq = atoi(env) != 0;
-    if (const char* env = getenv("D3_ATTN_WGS_PER_CU")) { const int v = atoi(env); if (v >= 1 && v <= 16) c->attn_wgs_per_cu = v; }
-    if (const char* env = getenv("D3_GEMV_HEAD_START")) { const int v = atoi(env); if (v >= 0 && v <= 64) c->gemv_head_start = v; }
-    if (const char* env = getenv("D3_GEMV_WGS_PER_CU")) {
-        const int v = atoi(env);
-        if (v >= 1 && v <= 8) c->gemv_wgs_per_cu = v;
-    }
+    c->prefill_by_seq = env_int("D3_PREFILL_BY_SEQ", 0, 1, 1) != 0;
+    c->attn_wgs_per_cu = env_int("D3_ATTN_WGS_PER_CU", 1, 16, c->attn_wgs_per_cu);
+    c->gemv_wgs_per_cu = env_int("D3_GEMV_WGS_PER_CU", 1, 8, c->gemv_wgs_per_cu);
     c->mfma_ok = mfma_fits(*desc);
     c->alu_ok = alu_fits(*desc);
     c->prof_class = D3_K_NONE; c->prof_used = 0;
@@ -205,30 +216,6 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->skip_row = -1;
     c->row_drop_begin.assign(desc->max_seq, 0);
     c->row_n_drop.assign(desc->max_seq, 0);
-
-    // persistent decode step: needs the block pointer table and zeroed barrier words on the device
-    c->mega_ok = false; c->mega_wgs = 0; c->bar_epoch = 0; c->debug_ts = nullptr;
-    {
-        const char* env = getenv("D3_PERSISTENT");
-        const bool want = env && atoi(env) != 0;        // opt-in until it beats one launch per projection
-        int per_cu = 1;
-        c->mega_depth = 8;
-        if (const char* e3 = getenv("D3_PERSISTENT_DEPTH")) { const int v = atoi(e3); if (v == 8 || v == 12) c->mega_depth = v; }
-        if (const char* e2 = getenv("D3_PERSISTENT_WGS_PER_CU")) { const int v = atoi(e2); if (v >= 1 && v <= 4) per_cu = v; }
-        if (want && desc->weight_dtype == D3_BF16 && desc->head_dim == 128 && c->alu_ok) {
-            MegaArgs probe{};
-            probe.d_model = desc->d_model; probe.H = desc->n_heads; probe.d_ffn = desc->d_ffn; probe.split_len = 8192;
-            const int fit = mega_max_workgroups(desc->kv_dtype, c->mega_depth, mega_lds_bytes(probe), c->n_cu);
-            int wgs = c->n_cu * per_cu;
-            if (wgs > fit) wgs = fit;
-            const long long waves = (long long)wgs * 8;
-            const long long most_units = desc->vocab / 2 > desc->d_ffn ? desc->vocab / 2 : desc->d_ffn;
-            if (wgs >= 8 && waves * 64 >= most_units && waves <= 4096) { c->mega_ok = true; c->mega_wgs = wgs; }
-        }
-        hipError_t e1 = hipMemcpy(c->at<d3_layer_weights>(lay.layer_ptrs), w->layers, (size_t)desc->n_layers * sizeof(d3_layer_weights), hipMemcpyHostToDevice);
-        if (e1 == hipSuccess) e1 = hipMemset(c->at<unsigned>(lay.barrier), 0, 512 * 4);
-        if (e1 != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: uploading the block table failed: %s", hipGetErrorString(e1)); }
-    }
 
     // rotary frequencies base^(-2j/hd), in binary64
     std::vector<double> inv(desc->head_dim / 2);
@@ -253,7 +240,6 @@ extern "C" int32_t d3_n_ctx(const d3_ctx* ctx) { return ctx ? ctx->n_ctx : 0; }
 namespace {
 
 int install_plan(d3_ctx* ctx, std::vector<int32_t>& keep, std::vector<int32_t>& drop, std::vector<int32_t>& ids) {
-    D3_HIP(hipMemcpy(ctx->at<int32_t>(ctx->lay.layer_table), ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     ctx->n_steps = (int)keep.size();
     ctx->keep.swap(keep); ctx->drop_begin.swap(drop); ctx->layer_ids.swap(ids);
     ctx->has_plan = true;
@@ -320,7 +306,7 @@ void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split
     if (want > kMaxSplits) want = kMaxSplits;
     // shortest split: 128 rows is what one workgroup of the vector-ALU kernel keeps in flight; shorter splits only add
     // partials to merge (batch 1, 640 rows: 10 splits of 64 rows 11.7 us a launch, 5 of 128 rows 10.2 us, 3 of 256 rows 12.4 us)
-    static const int min_len = [] { const char* e = getenv("D3_ATTN_MIN_SPLIT"); const int v = e ? atoi(e) : 0; return v >= 64 && v <= 65536 ? v / 64 * 64 : 128; }();
+    const int min_len = c->tn.attn_min_split;
     int len = ((ctx + want - 1) / want + 63) / 64 * 64;
     if (len < min_len) len = min_len;
     int n = (ctx + len - 1) / len;
@@ -339,7 +325,6 @@ int alu_projection(d3_ctx* c, GemvArgs g, int first, int count, int mode, bool n
         h.out = g.out + (size_t)(first + c0) * g.out_stride;
         h.ncols = count - c0 < per ? count - c0 : per;
         h.col0 = first + c0;
-        h.head_start = c->gemv_head_start;
         int rc = launch_gemv_alu(h, c->desc.weight_dtype, mode, norm, n_wg, s);
         if (rc != 0) return rc;
     }
@@ -420,7 +405,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             g.x_hi = n_hi; g.x_lo = n_lo; g.x_stride = dm; g.ssq_in = ssq; g.ssq_parts = ssq_parts;
             {
                 Timed t(c, D3_K_QKV, s);
-                D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+                D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, c->tn, s));
             }
             if (!rope_in_attn) {
                 RopeArgs r{};
@@ -447,7 +432,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         at.row0 = row0;
         {
             Timed t(c, D3_K_ATTN, s);
-            D3_HIP(launch_attention(at, d.kv_dtype, s));
+            D3_HIP(launch_attention(at, d.kv_dtype, c->tn.attn_mfma, s));
         }
 
         GemvArgs o{};
@@ -458,7 +443,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             if (mfma) {
                 o.x_hi = s_hi; o.x_lo = s_lo; o.x_stride = qdim;
                 o.out_hi = n_hi; o.out_lo = n_lo; o.gain_next = static_cast<const float*>(w.mlp_norm); o.ssq_out = ssq;
-                D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, s, &ssq_parts));
+                D3_HIP(launch_gemm_mfma(o, MODE_RESID, c->n_cu, c->tn, s, &ssq_parts));
             }
             else { o.x = attn_o; o.x_stride = qdim; D3_HIP(alu(o, 0, ncols, MODE_RESID, false)); }
         }
@@ -474,16 +459,14 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         if (mfma) {
             u.x_hi = n_hi; u.x_lo = n_lo; u.x_stride = dm; u.ssq_in = ssq; u.ssq_parts = ssq_parts;
             u.out = nullptr; u.out_hi = f_hi; u.out_lo = f_lo;
-            { Timed t(c, D3_K_GATE_UP, s); D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, s)); }
+            { Timed t(c, D3_K_GATE_UP, s); D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, c->tn, s)); }
             dn.x_hi = f_hi; dn.x_lo = f_lo; dn.x_stride = F;
             dn.out_hi = n_hi; dn.out_lo = n_lo; dn.gain_next = gain_after(e); dn.ssq_out = ssq;
-            { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, s, &ssq_parts)); }
+            { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, c->tn, s, &ssq_parts)); }
         } else {
             u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
-            if (e == n_ids - 1) u.debug_ts = c->debug_ts;      // debug timeline of the last block's gate/up launch
             { Timed t(c, D3_K_GATE_UP, s); D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true)); }
             dn.x = act; dn.x_stride = F;
-            if (e == n_ids - 1 && c->debug_ts) dn.debug_ts = c->debug_ts + 4096;
             { Timed t(c, D3_K_DOWN, s); D3_HIP(alu(dn, 0, ncols, MODE_RESID, false)); }
         }
         D3_HIP(dump(e + 1));
@@ -499,7 +482,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             g.x_hi = n_hi + (size_t)head->first_col * dm; g.x_lo = n_lo + (size_t)head->first_col * dm; g.x_stride = dm;
             g.ssq_in = ssq + (size_t)head->first_col * kSsqStride; g.ssq_parts = ssq_parts;
             Timed t(c, D3_K_LM_HEAD, s);
-            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, c->tn, s));
         } else {
             g.x = x + (size_t)head->first_col * dm; g.x_stride = dm; g.gain = static_cast<const float*>(c->final_norm);
             Timed t(c, D3_K_LM_HEAD, s);
@@ -507,33 +490,6 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
         }
         D3_HIP(launch_argmax(head->logits, d.vocab, head->n_cols, head->tok_out, s));
     }
-    return D3_OK;
-}
-
-// The whole decode step as one cooperative launch (decode_mega.hip).
-int decode_persistent(d3_ctx* c, const int32_t* tok_in, int step_i, int32_t* tok_out, float* logits, float* hidden_dump, hipStream_t s) {
-    const d3_model_desc& d = c->desc;
-    MegaArgs m{};
-    m.d_model = d.d_model; m.H = d.n_heads; m.H_kv = d.n_kv_heads; m.d_ffn = d.d_ffn; m.vocab = d.vocab; m.max_seq = d.max_seq;
-    m.kv_dtype = d.kv_dtype; m.eps = d.rms_eps;
-    m.tok_emb = c->tok_emb; m.final_norm = static_cast<const float*>(c->final_norm); m.lm_head = c->lm_head;
-    m.layers = c->at<d3_layer_weights>(c->lay.layer_ptrs);
-    m.k_cache = c->k_cache; m.v_cache = c->v_cache; m.kv_layer_bytes = c->kv_layer_bytes();
-    m.inv_freq = c->at<double>(c->lay.inv_freq);
-    m.layer_ids = c->at<int32_t>(c->lay.layer_table) + (size_t)step_i * d.n_layers;
-    m.n_ids = c->keep[step_i];
-    m.pos = c->n_ctx;
-    m.tok_in = tok_in; m.tok_out = tok_out; m.logits = logits; m.hidden_dump = hidden_dump;
-    pick_splits(c, 1, c->n_ctx + 1, c->mega_wgs, &m.split_len, &m.n_splits);
-    m.x = c->at<float>(c->lay.x); m.qkv = c->at<float>(c->lay.qkv); m.attn_o = c->at<float>(c->lay.attn_o); m.act = c->at<float>(c->lay.act);
-    m.part_o = c->at<float>(c->lay.part_o); m.part_ml = c->at<float>(c->lay.part_ml);
-    m.cand_val = c->at<float>(c->lay.cand_val); m.cand_idx = c->at<int>(c->lay.cand_idx);
-    m.tickets = c->at<int>(c->lay.tickets); m.rope_cs = c->at<float2>(c->lay.rope_cs);
-    m.barrier_state = c->at<unsigned>(c->lay.barrier); m.barrier_epoch = c->bar_epoch; m.max_spins = 1 << 21;
-    m.debug_ts = c->debug_ts; m.debug_stride = 10 * d.n_layers;
-    Timed t(c, D3_K_STEP, s);
-    D3_HIP(launch_decode_mega(m, d.kv_dtype, c->mega_depth, c->mega_wgs, s));
-    c->bar_epoch += 5u * (unsigned)m.n_ids + 2u;     // the launch passes exactly this many barriers
     return D3_OK;
 }
 
@@ -579,11 +535,8 @@ int prefill_impl(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32
         // row once per tile of queries instead of once per query
         // the matrix-core path takes 128 columns a pass (the weights are streamed once per pass); D3_PREFILL_COLS=64 halves that
         // (projections of large matrices split such a pass into two launches of 64 columns by themselves)
-        const char* cols_env = getenv("D3_PREFILL_COLS");                 // read per call: tests switch it
-        const int cols_v = cols_env ? atoi(cols_env) : 0;
-        const int forced_cols = cols_v == 64 || cols_v == 128 ? cols_v : 0;
-        const int wide_cols = forced_cols ? forced_cols : kPassCols;
-        const int chunk_cols = ctx->mfma_ok && gemm_mfma_wide_enabled() ? wide_cols : kMaxCols;
+        const int wide_cols = ctx->tn.prefill_cols ? ctx->tn.prefill_cols : kPassCols;
+        const int chunk_cols = ctx->mfma_ok && ctx->tn.mfma_wide ? wide_cols : kMaxCols;
         for (int b = 0; b < B; ++b) {
             for (int base = pos_begin == 0 ? ctx->row0[b] : 0; base < P;) {     // padding columns are not computed
                 const int ncols = P - base < chunk_cols ? P - base : chunk_cols;
@@ -643,18 +596,12 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     if (ctx->n_ctx >= ctx->desc.max_seq) return fail(D3_ERANGE, "d3_decode_step: cache is full (%d rows)", ctx->n_ctx);
     const int L = ctx->desc.n_layers, B = ctx->B;
     const int kept = ctx->keep[step_i];
-    int rc;
-    if (ctx->mega_ok && B == 1) {
-        rc = decode_persistent(ctx, tok_in, step_i, tok_out, logits ? logits : ctx->at<float>(ctx->lay.logits), hidden_dump,
-                               static_cast<hipStream_t>(hip_stream));
-    } else {
-        ColMap cm{0, B, 1, ctx->n_ctx};
-        HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
-        const bool keep_skip = ctx->fill_mode == D3_FILL_RECOMPUTE && kept < L;
-        rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
-                     static_cast<hipStream_t>(hip_stream), keep_skip ? ctx->drop_begin[step_i] + (L - kept) : -1);
-        ctx->skip_row = keep_skip && rc == D3_OK ? ctx->n_ctx : -1;
-    }
+    ColMap cm{0, B, 1, ctx->n_ctx};
+    HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
+    const bool keep_skip = ctx->fill_mode == D3_FILL_RECOMPUTE && kept < L;
+    const int rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
+                           static_cast<hipStream_t>(hip_stream), keep_skip ? ctx->drop_begin[step_i] + (L - kept) : -1);
+    ctx->skip_row = keep_skip && rc == D3_OK ? ctx->n_ctx : -1;
     if (rc != D3_OK) return rc;
     ctx->row_drop_begin[ctx->n_ctx] = ctx->drop_begin[step_i];
     ctx->row_n_drop[ctx->n_ctx] = L - kept;
@@ -676,7 +623,7 @@ int fill_recompute(d3_ctx* c, int pos_begin, int pos_end, hipStream_t s) {
                     c->n_ctx - 1, pos_begin, pos_end);
     const int p = pos_begin, first = c->row_drop_begin[p], n = c->row_n_drop[p];
     if (n == 0) return D3_OK;
-    if (c->skip_row != p) return fail(D3_ESTATE, "d3_fill_missing_kv: no kept residual for row %d (written by the prompt pass or the persistent step)", p);
+    if (c->skip_row != p) return fail(D3_ESTATE, "d3_fill_missing_kv: no kept residual for row %d (written by the prompt pass)", p);
     const d3_model_desc& d = c->desc;
     const int dm = d.d_model, hd = d.head_dim, kvdim = d.n_kv_heads * hd, B = c->B;
     const ColMap cm{0, B, 1, p};
@@ -697,7 +644,7 @@ int fill_recompute(d3_ctx* c, int pos_begin, int pos_end, hipStream_t s) {
             float* ssq = c->at<float>(c->lay.ssq);
             D3_HIP(launch_gain_split(h, dm, static_cast<const float*>(w.attn_norm), dm, B, n_hi, n_lo, ssq, s));
             g.x_hi = n_hi; g.x_lo = n_lo; g.x_stride = dm; g.ssq_in = ssq; g.ssq_parts = 1;
-            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, s));
+            D3_HIP(launch_gemm_mfma(g, MODE_STORE, c->n_cu, c->tn, s));
             RopeArgs r{};
             r.qkv = kv; r.k_cache = k_layer; r.v_cache = v_layer; r.rope_cs = rope_cs;
             r.cm = cm; r.ncols = B; r.H = 0; r.H_kv = d.n_kv_heads; r.hd = hd; r.max_seq = d.max_seq;
@@ -715,8 +662,6 @@ int fill_recompute(d3_ctx* c, int pos_begin, int pos_end, hipStream_t s) {
 extern "C" int d3_set_fill_mode(d3_ctx* ctx, int32_t mode) {
     if (!ctx) return fail(D3_EINVAL, "d3_set_fill_mode: ctx is NULL");
     if (mode != D3_FILL_COPY && mode != D3_FILL_RECOMPUTE) return fail(D3_EINVAL, "d3_set_fill_mode: unknown mode %d", mode);
-    if (mode == D3_FILL_RECOMPUTE && ctx->mega_ok)
-        return fail(D3_ESTATE, "d3_set_fill_mode: RECOMPUTE is not available with the persistent decode step");
     ctx->fill_mode = mode;
     ctx->skip_row = -1;
     return D3_OK;
@@ -764,7 +709,7 @@ extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
 
 extern "C" int d3_profile_select(d3_ctx* ctx, int32_t kernel_class) {
     if (!ctx) return fail(D3_EINVAL, "d3_profile_select: ctx is NULL");
-    if (kernel_class < D3_K_NONE || kernel_class > D3_K_STEP) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
+    if (kernel_class < D3_K_NONE || kernel_class > D3_K_LM_HEAD) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
     if (kernel_class != D3_K_NONE && ctx->prof_events.empty()) {
         ctx->prof_events.reserve(kMaxProfEvents);
         for (size_t i = 0; i < kMaxProfEvents; ++i) {
@@ -790,26 +735,5 @@ extern "C" int d3_profile_read(d3_ctx* ctx, double* total_ms, int64_t* launches)
     *total_ms = sum;
     *launches = (int64_t)(ctx->prof_used / 2);
     ctx->prof_used = 0;
-    return D3_OK;
-}
-
-extern "C" int d3_sync_check(d3_ctx* ctx, void* hip_stream) {
-    if (!ctx) return fail(D3_EINVAL, "d3_sync_check: ctx is NULL");
-    D3_HIP(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
-    unsigned abort_flag = 0;
-    D3_HIP(hipMemcpy(&abort_flag, ctx->at<unsigned>(ctx->lay.barrier) + 288, sizeof(unsigned), hipMemcpyDeviceToHost));
-    if (abort_flag != 0) {
-        D3_HIP(hipMemset(ctx->at<unsigned>(ctx->lay.barrier), 0, 512 * 4));
-        ctx->bar_epoch = 0;
-        return fail(D3_EDEVICE, "d3_sync_check: a persistent decode step gave up waiting at a grid barrier; its outputs are invalid");
-    }
-    return D3_OK;
-}
-
-extern "C" int d3_uses_persistent_step(const d3_ctx* ctx) { return ctx && ctx->mega_ok ? ctx->mega_wgs : 0; }
-
-extern "C" int d3_debug_timeline(d3_ctx* ctx, void* device_buffer) {
-    if (!ctx) return fail(D3_EINVAL, "d3_debug_timeline: ctx is NULL");
-    ctx->debug_ts = static_cast<unsigned long long*>(device_buffer);
     return D3_OK;
 }

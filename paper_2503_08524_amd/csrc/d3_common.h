@@ -17,7 +17,7 @@ constexpr int kSsqStride = 512;    // partial sums of squares kept per column (o
 typedef uint16_t bf16_t;           // bf16 bit pattern
 typedef _Float16 f16_t;            // IEEE half (KV cache only)
 
-// bytes per KV-cache element for a d3_dtype value (0 f32, 1 bf16, 2 f16)
+// bytes per KV-cache element for a d3_dtype value (0 f32, 2 f16)
 inline int kv_elem_bytes(int kv_dtype) { return kv_dtype == 0 ? 4 : 2; }
 
 // Which (sequence, position, token) a column of the current pass stands for.
@@ -108,15 +108,30 @@ struct GemvArgs {
     // group (zero between launches)
     float* part;
     int* part_tickets;
-    unsigned long long* debug_ts;   // optional: per-workgroup 100 MHz timestamps (entry, staged, done)
-    int head_start;                 // pause (units of 512 clocks) between issuing the activation loads and the weight preload
 };
+
+// Launch-shape overrides for measurements, read from the environment ONCE by d3_create (0 / default = the library's
+// own choice).  D3_MFMA_RT, D3_MFMA_WAVES: row tiles per workgroup and waves of the narrow matrix-core projection;
+// D3_MFMA_WIDE=0: no panel kernel (passes are limited to kMaxCols columns); D3_WIDE_RT, D3_WIDE_KS: row tiles per wave
+// and K slices of the panel kernel; D3_WIDE_SPLIT_MB: matrix size above which a pass of more than 64 columns runs as
+// two 64-column launches; D3_ATTN_MFMA=0: grouped-query and query-tile attention on the vector ALUs;
+// D3_ATTN_MIN_SPLIT: shortest context split; D3_PREFILL_COLS: 64 or 128 columns per prompt chunk.
+struct Tuning {
+    int mfma_rt = 0, mfma_waves = 0;
+    bool mfma_wide = true;
+    int wide_rt = 0, wide_ks = 0;
+    size_t wide_split_mb = 300;
+    bool attn_mfma = true;
+    int attn_min_split = 128;
+    int prefill_cols = 0;
+};
+Tuning tuning_from_env();
 
 // returns hipError_t as int
 int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, int n_wg, hipStream_t s);
-int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups = nullptr);
-int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups);   // 17..kPassCols columns
-bool gemm_mfma_wide_enabled();   // false: D3_MFMA_WIDE=0, passes are limited to kMaxCols columns   // n_groups: workgroups launched (= parts written to ssq_out)
+// n_groups: workgroups launched (= parts written to ssq_out)
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups = nullptr);
+int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups);   // 17..kPassCols columns
 size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
 
 // first step of a pass on the MFMA path: hi + lo = x * gain (bf16 halves), ssq[col * kSsqStride] = sum(x^2)
@@ -157,7 +172,7 @@ struct AttnArgs {
     bf16_t* out_hi;        // optional split copy
     bf16_t* out_lo;
 };
-int launch_attention(const AttnArgs& a, int kv_dtype, hipStream_t s);
+int launch_attention(const AttnArgs& a, int kv_dtype, bool use_mfma, hipStream_t s);
 
 int launch_argmax(const float* logits, int vocab, int ncols, int32_t* out, hipStream_t s);
 

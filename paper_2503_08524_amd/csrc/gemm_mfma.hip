@@ -253,13 +253,6 @@ __global__ __launch_bounds__(512) void gemm_mfma_kernel(GemvArgs a) {   // <= 8 
     }
 }
 
-int env_int(const char* name, int lo, int hi) {
-    const char* e = getenv(name);
-    if (!e) return 0;
-    const int v = atoi(e);
-    return v >= lo && v <= hi ? v : 0;
-}
-
 template <int NT, int MODE, bool PACK>
 int launch_rt(const GemvArgs& a, int rt, int tiles, int waves, size_t lds, hipStream_t s) {
 #define D3_LAUNCH(RT) hipLaunchKernelGGL((gemm_mfma_kernel<NT, MODE, RT, PACK>), dim3(tiles / RT), dim3(64 * waves), lds, s, a)
@@ -279,20 +272,14 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 
 }  // namespace
 
-// D3_MFMA_WIDE=0 keeps 17..32 columns on this file's kernel (for comparisons) and limits a pass to 32 columns
-bool gemm_mfma_wide_enabled() {
-    static const bool on = [] { const char* e = getenv("D3_MFMA_WIDE"); return !(e && e[0] == '0'); }();
-    return on;
-}
-
 // Requirements (checked by the caller): bf16 weights; K % 32 == 0; total_rows and every rows[m]
 // multiples of 16; 1 <= ncols <= 32; x_hi/x_lo hold 32 rows of x_stride elements (rows beyond
 // ncols may hold anything finite or not: their columns are never written); with ssq_out, total_rows / 16 <=
 // kSsqStride (every workgroup owns a slot).
-int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
+int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
-    if (nt == 2 && a.part && gemm_mfma_wide_enabled()) return launch_gemm_mfma_wide(a, mode, n_cu, s, n_groups);
+    if (nt == 2 && a.part && tn.mfma_wide) return launch_gemm_mfma_wide(a, mode, n_cu, tn, s, n_groups);
     if (a.ncols > kMaxCols) return (int)hipErrorInvalidValue;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;                  // 128-k turns along K
@@ -304,7 +291,7 @@ int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* 
     // (rows[m] % (16 RT) == 0).
     int best_rt = 1, best_waves = 4;
     const int rt_max = (mode == MODE_SWIGLU ? 2 : 4) / nt;      // register budget: A tiles x column tiles per wave (more spills: measured 1.5-2.5x slower)
-    const int rt_forced = env_int("D3_MFMA_RT", 1, 4), waves_forced = env_int("D3_MFMA_WAVES", 1, 8);
+    const int rt_forced = tn.mfma_rt, waves_forced = tn.mfma_waves;
     for (int rt = rt_max; rt >= 1; rt /= 2) {
         if (tiles % rt != 0) continue;
         bool aligned = true;

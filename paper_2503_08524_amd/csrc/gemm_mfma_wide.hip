@@ -347,13 +347,6 @@ __global__ __launch_bounds__(W * 64, (MODE == MODE_SWIGLU && CT == 2) ? 3 : 1) v
     }
 }
 
-int env_int(const char* name, int lo, int hi) {
-    const char* e = getenv(name);
-    if (!e) return 0;
-    const int v = atoi(e);
-    return v >= lo && v <= hi ? v : 0;
-}
-
 template <int MODE, int RT, int CT, int W>
 int launch_one(const GemvArgs& a, int groups, int ks, hipStream_t s) {
     constexpr size_t lds = (size_t)(2 * 2 * CT + W) * kTile;
@@ -389,14 +382,14 @@ int launch_rt(const GemvArgs& a, int ct, int rt, int groups, int ks, hipStream_t
 // kGemmPartTickets zeroed counters (the kernel leaves them zero).
 namespace {
 
-int launch_config(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups, int force_ct);
+int launch_config(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups, int force_ct);
 
 // Column halves of a pass of more than 64 columns, both with the 64-column kernel (the same row groups, so the partial
 // sums of squares of all columns have one layout).
-int launch_halves(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
+int launch_halves(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups) {
     GemvArgs lo = a;
     lo.ncols = 64;
-    int rc = launch_config(lo, mode, n_cu, s, n_groups, 4);
+    int rc = launch_config(lo, mode, n_cu, tn, s, n_groups, 4);
     if (rc != 0) return rc;
     GemvArgs hi = a;
     hi.ncols = a.ncols - 64;
@@ -405,26 +398,24 @@ int launch_halves(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_g
     if (hi.out_hi) { hi.out_hi += (size_t)64 * a.out_stride; hi.out_lo += (size_t)64 * a.out_stride; }
     if (hi.ssq_in) hi.ssq_in += (size_t)64 * kSsqStride;
     if (hi.ssq_out) hi.ssq_out += (size_t)64 * kSsqStride;
-    return launch_config(hi, mode, n_cu, s, nullptr, 4);
+    return launch_config(hi, mode, n_cu, tn, s, nullptr, 4);
 }
 
 }  // namespace
 
-int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups) {
+int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups) {
     // More than 64 columns: one launch of the 128-column kernel (four waves per workgroup) when the matrix is small enough
     // for its fixed costs to matter, else two of the 64-column kernel, whose eight-wave workgroups stream a large matrix
     // faster (70B shape, per 128 columns: gate/up 940 MB 396 against 330 us, down 470 MB 252 against 224 us; QKV 168 MB 85
     // against 95 us, O 134 MB 84 against 100 us)
     const size_t weight_bytes = (size_t)a.total_rows * a.K * 2 * (mode == MODE_SWIGLU ? 2 : 1);
-    size_t split_mb = 300;
-    if (const char* e = getenv("D3_WIDE_SPLIT_MB")) { const long v = atol(e); if (v >= 0 && v <= (1 << 20)) split_mb = (size_t)v; }   // read per call: tests switch it
-    if (a.ncols > 64 && weight_bytes > (split_mb << 20)) return launch_halves(a, mode, n_cu, s, n_groups);
-    return launch_config(a, mode, n_cu, s, n_groups, 0);
+    if (a.ncols > 64 && weight_bytes > (tn.wide_split_mb << 20)) return launch_halves(a, mode, n_cu, tn, s, n_groups);
+    return launch_config(a, mode, n_cu, tn, s, n_groups, 0);
 }
 
 namespace {
 
-int launch_config(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_groups, int force_ct) {
+int launch_config(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups, int force_ct) {
     const int tiles = a.total_rows / 16;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int turns = (a.K / 32 + U - 1) / U;
@@ -439,12 +430,12 @@ int launch_config(const GemvArgs& a, int mode, int n_cu, hipStream_t s, int* n_g
     // tiles for that (down-projection: 128 workgroups, 32.6 -> 44 us)
     if (ct == 4 && mode == MODE_STORE) rt = 2;
     if (ct == 8) rt = mode == MODE_STORE ? 2 : 1;
-    if (const int v = env_int("D3_WIDE_RT", 1, 2)) if (ct != 8 && (v == 1 || mode != MODE_SWIGLU)) rt = v;
+    if (const int v = tn.wide_rt) if (ct != 8 && (v == 1 || mode != MODE_SWIGLU)) rt = v;
     int groups = (tiles + w * rt - 1) / (w * rt);
     // up to 32 columns: three workgroups fit a CU; up to 64: one (its panels fill most of the LDS)
     int ks = (ct == 8 ? 1 : ct == 4 ? 2 : 3) * n_cu / groups;
     if (ks > 8) ks = 8;
-    if (const int v = env_int("D3_WIDE_KS", 1, 64)) ks = v;
+    if (const int v = tn.wide_ks) ks = v;
     if (ks > turns / 4) ks = turns / 4;
     if (ks < 1) ks = 1;
     while (ks > 1 && (size_t)groups * ks * w * (rt * sw * ct * 4) * 64 * sizeof(float) > kGemmPartBytes) --ks;

@@ -254,13 +254,11 @@ __device__ __forceinline__ void gemv_fma_step(const u32x4& w0, const u32x4& w1, 
 // Store one element of a new cache row in the cache's element type.
 __device__ __forceinline__ void kv_store(void* base, size_t idx, int kv_dtype, float v) {
     if (kv_dtype == 0) static_cast<float*>(base)[idx] = v;
-    else if (kv_dtype == 1) static_cast<bf16_t*>(base)[idx] = (bf16_t)f32_to_bf16(v);
     else static_cast<f16_t*>(base)[idx] = (f16_t)fminf(fmaxf(v, -65504.f), 65504.f);
 }
 // The value a later read of that cache element returns.
 __device__ __forceinline__ float kv_round(int kv_dtype, float v) {
     if (kv_dtype == 0) return v;
-    if (kv_dtype == 1) return bf16_to_f32(f32_to_bf16(v));
     return (float)(f16_t)fminf(fmaxf(v, -65504.f), 65504.f);
 }
 

@@ -31,19 +31,15 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_alu_kernel(GemvArgs a) {
     // band of the matrix (spread over every memory channel); numbering the waves workgroup-fastest hands the units
     // that do not divide evenly to different workgroups, one each.
     const int gw = wave * gridDim.x + blockIdx.x, nw = gridDim.x * kGemvWaves;
-    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 0] = wall_clock64();
     GemvStageRegs<NC, R> regs;
     GemvPipe<W, kGemvDepth> pipe;
     gemv_stage_issue<NC, NORM, false, kGemvThreads, R>(a, tid, regs);          // activations first ...
-    for (int i = 0; i < a.head_start; ++i) __builtin_amdgcn_s_sleep(8);          // ... with a head start over every workgroup's weights
     gemv_preload<W, MODE, kGemvDepth>(a, gw, nw, pipe);                          // ... the weight stream right behind them
     gemv_stage_commit<W, NC, NORM, false, kGemvThreads, R>(a, tid, xs, regs, red);
     __syncthreads();
-    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 1] = wall_clock64();
     float rinv[NC];
     gemv_inv_rms<NC, NORM, kGemvWaves>(a, red, rinv);
     gemv_run<W, NC, MODE, kGemvDepth, false>(a, xs, gw, nw, pipe, ep[wave], rinv);
-    if (a.debug_ts && tid == 0) a.debug_ts[blockIdx.x * 4 + 2] = wall_clock64();
 }
 
 template <typename W, int NC>

@@ -89,7 +89,6 @@ __global__ __launch_bounds__(256) void gain_split_kernel(const float* __restrict
 template <typename T>
 __device__ __forceinline__ void store_kv(T* p, float v);
 template <> __device__ __forceinline__ void store_kv<float>(float* p, float v) { *p = v; }
-template <> __device__ __forceinline__ void store_kv<bf16_t>(bf16_t* p, float v) { *p = (bf16_t)f32_to_bf16(v); }
 template <> __device__ __forceinline__ void store_kv<f16_t>(f16_t* p, float v) { *p = (f16_t)fminf(fmaxf(v, -65504.f), 65504.f); }
 
 template <typename T>
@@ -204,8 +203,8 @@ int launch_gain_split(const float* x, int x_stride, const float* gain, int K, in
 int launch_rope_append(const RopeArgs& a, int kv_dtype, hipStream_t s) {
     dim3 grid(a.H + 2 * a.H_kv, a.ncols);
     if (kv_dtype == 0) hipLaunchKernelGGL(rope_append_kernel<float>, grid, dim3(64), 0, s, a);
-    else if (kv_dtype == 1) hipLaunchKernelGGL(rope_append_kernel<bf16_t>, grid, dim3(64), 0, s, a);
-    else hipLaunchKernelGGL(rope_append_kernel<f16_t>, grid, dim3(64), 0, s, a);
+    else if (kv_dtype == 2) hipLaunchKernelGGL(rope_append_kernel<f16_t>, grid, dim3(64), 0, s, a);
+    else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ def oracle_threads() -> int:
 
 def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: int, forced: Optional[np.ndarray] = None,
                  kv_dtype: Optional[str] = None, max_seq: Optional[int] = None, min_keep: int = 0, fill_each_step: bool = False,
-                 decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None, persistent: Optional[bool] = None,
+                 decoder=None, pos_begin: int = 0, max_batch: Optional[int] = None,
                  fill_mode: int = 0, linear=None, lengths=None):
     """Prompt pass + G-1 decode steps through the C ABI.  forced: [B][G-1] tokens fed instead of the GPU's own.
     linear: (keep_first, keep_last) of a linear-decay schedule to follow instead of the power law.
@@ -33,18 +33,7 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
     dev = "cuda:0"
     if decoder is None:
         w_dev = binding.weights_to_device(shape, w_np, dev)
-        old = os.environ.get("D3_PERSISTENT")
-        if persistent is not None:
-            os.environ["D3_PERSISTENT"] = "1" if persistent else "0"    # read by d3_create
-        try:
-            decoder = binding.Decoder(shape, w_dev, max_batch or B, max_seq or (pos_begin + P + G), kv_dtype=kv_dtype, device=dev)
-        finally:
-            if old is None:
-                os.environ.pop("D3_PERSISTENT", None)
-            else:
-                os.environ["D3_PERSISTENT"] = old
-        if persistent is not None:
-            assert (decoder.persistent_workgroups > 0) == persistent
+        decoder = binding.Decoder(shape, w_dev, max_batch or B, max_seq or (pos_begin + P + G), kv_dtype=kv_dtype, device=dev)
     L = shape.L
     if linear is not None:
         keep, drop, _ = binding.d3_plan_depth_linear(L, linear[0], linear[1], start, max(G, 2))
@@ -76,7 +65,7 @@ def gpu_generate(shape, w_np, prompts: np.ndarray, G: int, alpha: float, start: 
         out_tokens.append(cur.cpu().numpy().copy())
         out_logits.append(logits.cpu().numpy().copy())
         out_hidden.append(hid_i.cpu().numpy().copy())
-    decoder.sync_check()
+    decoder.synchronize()
     return {"tokens": np.stack(out_tokens), "logits": np.stack(out_logits), "hidden": out_hidden, "decoder": decoder}
 
 

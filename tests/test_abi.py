@@ -96,11 +96,13 @@ def test_workspace_size_and_shape_checks(lib):
         n = d3.d3_workspace_size(s, "f16" if s.dtype == "bf16" else "f32", 8, 2048)
         assert n > 0 and n % 256 == 0 and n < 2 ** 31
     bad = d3_inputs.ModelShape("bad", L=2, d=256, H=4, H_kv=3, hd=64, F=688, V=1024)
-    assert d3.d3_workspace_size(bad, "bf16", 1, 64) == 0
+    assert d3.d3_workspace_size(bad, "f16", 1, 64) == 0
     assert "n_kv_heads" in lib.d3_last_error().decode()
     bad = d3_inputs.ModelShape("bad", L=2, d=256, H=4, H_kv=4, hd=80, F=688, V=1024)
-    assert d3.d3_workspace_size(bad, "bf16", 1, 64) == 0
+    assert d3.d3_workspace_size(bad, "f16", 1, 64) == 0
     assert d3.d3_workspace_size(d3_inputs.TINY, "f32", 33, 64) == 0          # max_batch beyond 32
+    assert d3.d3_workspace_size(d3_inputs.LLAMA_7B, "bf16", 1, 64) == 0       # a bf16 cache misses the logit tolerance
+    assert "D3_BF16" in lib.d3_last_error().decode()
 
 
 def test_null_context_is_an_error_not_a_crash(lib):

@@ -1,0 +1,89 @@
+"""GPU parity at the depth the benchmark runs: ALL L blocks of the 7B / 13B / 70B shapes on the GPU against
+the oracle running ALL L blocks, every hidden slot (relative L2 <= 1e-2 after every executed block) and the complete
+logits (max abs error <= 2e-2) of every step.
+
+The L blocks point at one weight set (the host draws one block; each block still has its own cache rows, because its
+input differs), the prompt is short (the oracle runs every prompt token through every block), the tokens are
+teacher-forced, and alpha = 0.97 keeps L, floor(0.97 L), ... blocks, so every step runs nearly the full depth through the
+same kernels, in the same launch shapes per projection, as the benchmark configurations: vector-ALU GEMV at batch 1,
+packed narrow matrix-core projections at batch 4 and 8, the K-sliced panel kernel at batch 32, grouped-query attention
+on the matrix cores at the 70B shape."""
+import functools
+
+import numpy as np
+import pytest
+
+import d3_inputs
+from tests import helpers
+
+pytestmark = pytest.mark.gpu
+
+
+@functools.lru_cache(maxsize=1)
+def _one_block_weights(name):
+    return d3_inputs.make_weights(d3_inputs.SHAPES[name].truncated(1), 0)
+
+
+def _depth_case(name, B, P, G, sampled, alpha=0.97, kv_dtype=None):
+    from oracle import oracle
+    from paper_2503_08524_amd import binding
+
+    full = d3_inputs.SHAPES[name]
+    one = full.truncated(1)
+    w1 = _one_block_weights(name)
+    w_tied = dict(w1)
+    w_tied["layers"] = [w1["layers"][0]] * full.L
+    start = d3_inputs.start_layer_from_fraction(full.L, 0.6)
+    prompts = d3_inputs.make_prompt(B, P, full.V, seed=1)
+    forced = d3_inputs.make_prompt(B, G - 1, full.V, seed=41)
+    keep, _, _ = binding.d3_plan_depth(full.L, alpha, start, 0, G)
+    assert keep[0] == full.L and keep[G - 1] >= full.L - 4 * G
+
+    dev = binding.weights_to_device(one, w1)
+    dev_tied = dict(dev)
+    dev_tied["layers"] = [dev["layers"][0]] * full.L
+    dec = binding.Decoder(full, dev_tied, B, P + G, kv_dtype=kv_dtype)
+    print(f"case all-blocks {name} L={full.L} B={B} P={P} G={G} alpha={alpha} kv={kv_dtype or 'default'} keep={keep.tolist()}", flush=True)
+    gpu = helpers.gpu_generate(full, None, prompts, G, alpha, start, forced=forced, decoder=dec)
+    dec.close()
+
+    oracle.set_threads(helpers.oracle_threads())
+    model = oracle.OracleModel(full, w_tied)
+    per_slot = np.zeros(full.L + 1)          # worst relative L2 of the hidden state after e executed blocks
+    per_step = np.zeros(G)                   # worst logit error of step i
+    for b in sampled:
+        gen = oracle.generate(model, prompts[b], G, alpha, start, forced=forced[b])
+        print(f"  oracle done for sequence {b}", flush=True)
+        for i in range(G):
+            hr, hg = gen.hidden[i], gpu["hidden"][i][:, b, :].astype(np.float64)
+            assert hr.shape == hg.shape == (keep[i] + 1, full.d)
+            rel = np.linalg.norm(hg - hr, axis=1) / np.linalg.norm(hr, axis=1)
+            per_slot[: keep[i] + 1] = np.maximum(per_slot[: keep[i] + 1], rel)
+            per_step[i] = max(per_step[i], float(np.abs(gpu["logits"][i][b].astype(np.float64) - gen.logits[i]).max()))
+            top2 = np.partition(gen.logits[i], -2)[-2:]
+            if top2[1] - top2[0] > helpers.TOKEN_MARGIN:
+                assert int(gpu["tokens"][i][b]) == gen.tokens[i], f"token seq {b} step {i}"
+    print("  hidden rel L2 after e blocks: " + " ".join(f"{e}:{v:.1e}" for e, v in enumerate(per_slot)), flush=True)
+    print("  logits max abs err per step (step 0 = prompt pass): " + " ".join(f"{v:.2e}" for v in per_step), flush=True)
+    assert per_slot.max() <= helpers.HIDDEN_REL_L2, f"hidden rel L2 {per_slot.max():.3e} at slot {int(per_slot.argmax())}"
+    assert per_step.max() <= helpers.LOGIT_ATOL, f"logits max abs err {per_step.max():.3e} at step {int(per_step.argmax())}"
+
+
+@pytest.mark.timeout(600)
+def test_all_32_blocks_7b_batch1_vector_alu_gemv():
+    _depth_case("llama-7b", 1, 16, 4, sampled=(0,))
+
+
+@pytest.mark.timeout(600)
+def test_all_32_blocks_7b_batch32_panel_kernel():
+    _depth_case("llama-7b", 32, 16, 4, sampled=(0, 31))
+
+
+@pytest.mark.timeout(600)
+def test_all_40_blocks_13b_batch4_packed_matrix_core_projections():
+    _depth_case("llama-13b", 4, 16, 4, sampled=(0, 3))
+
+
+@pytest.mark.timeout(900)
+def test_all_80_blocks_70b_batch8_grouped_query_attention():
+    _depth_case("llama-70b", 8, 8, 3, sampled=(2, 7))

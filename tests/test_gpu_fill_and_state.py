@@ -19,7 +19,7 @@ def _cache_rows(dec, layer, seq, pos):
     return k, v
 
 
-@pytest.mark.parametrize("start,kv", [(2, "f16"), (0, "bf16"), (4, "f32")])
+@pytest.mark.parametrize("start,kv", [(2, "f16"), (0, "f16"), (4, "f32")])
 @pytest.mark.parametrize("lazy", [False, True])
 def test_fill_copies_the_source_block_and_matches_oracle(start, kv, lazy):
     import torch
@@ -36,7 +36,7 @@ def test_fill_copies_the_source_block_and_matches_oracle(start, kv, lazy):
     torch.cuda.synchronize()
     model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=P + G + 8)
     L = shape.L
-    tol = {"f32": 2e-5, "f16": 4e-3, "bf16": 3e-2}[kv]
+    tol = {"f32": 2e-5, "f16": 4e-3}[kv]
     for b, gen in enumerate(gens):
         oracle.fill_generated_rows(gen, P, G)
         for i in range(1, G):
@@ -179,7 +179,7 @@ def _check_recomputed_rows(dec, gens, shape, P, G, tol, lengths=None):
     return worst
 
 
-@pytest.mark.parametrize("B,start,kv", [(1, 2, "f16"), (1, 0, "f32"), (3, 2, "f16"), (3, 4, "bf16"), (2, 0, "f16")])
+@pytest.mark.parametrize("B,start,kv", [(1, 2, "f16"), (1, 0, "f32"), (3, 2, "f16"), (3, 4, "f32"), (2, 0, "f16")])
 def test_recompute_fill_matches_oracle_and_continuation_reads_it(B, start, kv):
     """RECOMPUTE fill: K/V of every dropped block recomputed from the hidden state copied through the drop window
     (batch 1: the fused QKV kernel without q heads; batch >= 2: the matrix-core path), then a second request on the
@@ -200,7 +200,7 @@ def test_recompute_fill_matches_oracle_and_continuation_reads_it(B, start, kv):
     dec = gpu["decoder"]
     torch.cuda.synchronize()
     model, gens = helpers.oracle_generate(shape, w, prompts, G, alpha, start, forced=forced, max_seq=max_seq)
-    tol = {"f32": 5e-5, "f16": 4e-3, "bf16": 3e-2}[kv]
+    tol = {"f32": 5e-5, "f16": 4e-3}[kv]
     worst = _check_recomputed_rows(dec, gens, shape, P, G, tol)
     n_rows = P + G - 1
     gpu2 = helpers.gpu_generate(shape, w, prompts2, G2, alpha, start, forced=forced2, decoder=dec, pos_begin=n_rows)
@@ -240,7 +240,7 @@ def test_schedule_whose_depth_rises_again_reads_the_filled_rows(mode):
         dec.decode_step(cur, i, nxt, logits=logits)
         dec.fill_missing_kv(dec.n_ctx - 1, dec.n_ctx, fm)
         got.append(logits.cpu().numpy().copy())
-    dec.sync_check()
+    dec.synchronize()
     ids = binding.d3_plan_from_table(L, keep, drop)
     oracle.set_threads(helpers.oracle_threads())
     model = oracle.OracleModel(shape, w)
@@ -344,7 +344,7 @@ def test_recompute_fill_call_rules():
     assert status(lambda: dec.fill_missing_kv(6, 7, binding.D3_FILL_RECOMPUTE)) == -4
     dec.fill_missing_kv(7, 8, binding.D3_FILL_RECOMPUTE)
     dec.fill_missing_kv(6, 7, binding.D3_FILL_COPY)                                     # COPY stays available for any row
-    dec.sync_check()
+    dec.synchronize()
     dec.close()
 
 

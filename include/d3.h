@@ -171,6 +171,22 @@ int d3_prefill_ragged(d3_ctx *ctx, const int32_t *tokens, const int32_t *lengths
 int d3_decode_step(d3_ctx *ctx, const int32_t *tok_in, int32_t step_i, int32_t *tok_out,
                    float *logits, float *hidden_dump, void *hip_stream);
 
+/* d3_decode_step for callers that cannot allocate device memory and have none to lend: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, state changes, results and
+ * errors as d3_decode_step, but every intermediate of the step (residual stream, activations, attention
+ * partials, arrival counters, the rotary table) lives in a static device array inside the library,
+ * d3_static_scratch_bytes() = 32 MiB per GPU, held from the first d3_create on that GPU until the process
+ * ends, instead of the context's workspace (which is left untouched).  The call allocates nothing, on the host or on
+ * the device, and enqueues kernels and device-to-device copies only (no memset nodes).  D3_ESHAPE if a step of
+ * this model at desc.max_batch needs more than the array holds (the 7B, 13B and 70B shapes fit up to batch 16);
+ * D3_ESTATE with D3_FILL_RECOMPUTE (that fill reads a residual kept in the workspace).  All contexts on a GPU
+ * share the one array: calls of this function that overlap on one GPU (different streams or threads) race;
+ * calls on one stream, also of different contexts, are safe, since the array carries nothing from one call to the
+ * next.  Steps of one request may mix d3_decode_step and d3_decode_step_static freely. */
+int d3_decode_step_static(d3_ctx *ctx, const int32_t *tok_in, int32_t step_i, int32_t *tok_out,
+                          float *logits, float *hidden_dump, void *hip_stream);
+size_t d3_static_scratch_bytes(void);
+
 /* Missing-state fill (Section 1, challenge (i); Section 3.2): for every cache
  * row p in [pos_begin, pos_end) that a decode step wrote with a reduced depth,
  * and every block l that step dropped, K[l][.][p], V[l][.][p] <- K[src][.][p],

@@ -68,6 +68,8 @@ def load_library() -> C.CDLL:
         lib.d3_prefill.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, vp]
         lib.d3_prefill_ragged.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp, vp]
         lib.d3_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+        lib.d3_decode_step_static.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+        lib.d3_static_scratch_bytes.restype = C.c_size_t
         lib.d3_fill_missing_kv.argtypes = [vp, i32, i32, i32, vp]
         lib.d3_set_fill_mode.argtypes = [vp, i32]
         lib.d3_n_ctx.argtypes = [vp]
@@ -221,6 +223,11 @@ class Decoder:
     def decode_step(self, tok_in, step_i: int, tok_out, logits=None, hidden_dump=None) -> None:
         _check(self.lib.d3_decode_step(self.ctx, tok_in.data_ptr(), step_i, tok_out.data_ptr(), _ptr(logits),
                                        _ptr(hidden_dump), self._stream()))
+
+    def decode_step_static(self, tok_in, step_i: int, tok_out, logits=None, hidden_dump=None) -> None:
+        """decode_step with its intermediates in the library's static scratch array (no workspace use, no allocation)."""
+        _check(self.lib.d3_decode_step_static(self.ctx, tok_in.data_ptr(), step_i, tok_out.data_ptr(), _ptr(logits),
+                                              _ptr(hidden_dump), self._stream()))
 
     def fill_missing_kv(self, pos_begin: int, pos_end: int, mode: int = D3_FILL_COPY) -> None:
         _check(self.lib.d3_fill_missing_kv(self.ctx, pos_begin, pos_end, mode, self._stream()))

@@ -1,6 +1,7 @@
 // C ABI of the D^3 decode path: context, argument checks, and the per-step orchestration
 // that launches only the blocks the schedule keeps (Section 3.4).  All device memory is the
 // caller's; this file owns host state only.
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -57,8 +58,10 @@ int check_desc(const d3_model_desc* d) {
     return D3_OK;
 }
 
-Layout make_layout(const d3_model_desc& d) {
-    const size_t C = kPassCols, qdim = (size_t)d.n_heads * d.head_dim;
+// C columns of fp32 activations, CS columns of bf16 hi/lo splits (the matrix-core projections read whole column tiles:
+// at least 32 of them must exist), the K-slice partials of the panel kernel only when a pass can have more than 16 columns.
+Layout make_layout(const d3_model_desc& d, size_t C, size_t CS, bool with_gemm_part) {
+    const size_t qdim = (size_t)d.n_heads * d.head_dim;
     const size_t qkv_dim = (size_t)(d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
     const size_t s_dim = qdim > (size_t)d.d_model ? qdim : (size_t)d.d_model;
     Layout l{};
@@ -72,22 +75,24 @@ Layout make_layout(const d3_model_desc& d) {
     l.part_ml = take(C * d.n_heads * kMaxSplits * 2 * 4);
     l.tickets = take(C * d.n_heads * 4);
     l.logits = take(C * (size_t)d.vocab * 4);
-    l.s_hi = take(C * s_dim * 2);
-    l.s_lo = take(C * s_dim * 2);
-    l.f_hi = take(C * (size_t)d.d_ffn * 2);
-    l.f_lo = take(C * (size_t)d.d_ffn * 2);
+    l.s_hi = take(CS * s_dim * 2);
+    l.s_lo = take(CS * s_dim * 2);
+    l.f_hi = take(CS * (size_t)d.d_ffn * 2);
+    l.f_lo = take(CS * (size_t)d.d_ffn * 2);
     l.inv_freq = take((size_t)d.head_dim / 2 * 8);
     l.rope_cs = take(C * (size_t)d.head_dim / 2 * 8);
-    l.n_hi = take(C * d.d_model * 2);
-    l.n_lo = take(C * d.d_model * 2);
+    l.n_hi = take(CS * d.d_model * 2);
+    l.n_lo = take(CS * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
     l.h_skip = take(C * d.d_model * 4);
-    l.gemm_part = take(kGemmPartBytes);
+    l.gemm_part = take(with_gemm_part ? kGemmPartBytes : 0);
     l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
     l.row0 = take(kPassCols * 4);
     l.total = o;
     return l;
 }
+// The caller's workspace serves prompt chunks of up to kPassCols columns.
+Layout make_layout(const d3_model_desc& d) { return make_layout(d, kPassCols, kPassCols, true); }
 
 }  // namespace
 
@@ -117,6 +122,15 @@ Tuning tuning_from_env() {
 }
 }  // namespace d3
 
+// d3_decode_step_static: the step's intermediates live here instead of the context's workspace.  One array per GPU,
+// held until the process ends; calls that overlap on one GPU share it (and race).
+constexpr size_t kStaticScratchBytes = 32u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up by d3_create on that GPU
+}  // namespace
+
 struct d3_ctx {
     d3_model_desc desc;
     std::vector<d3_layer_weights> layers;
@@ -124,6 +138,8 @@ struct d3_ctx {
     char *k_cache, *v_cache, *ws;
     Layout lay;
     int n_cu;
+    int dev;                      // HIP device the context was made on
+    std::vector<double> inv_freq; // rotary frequencies base^(-2j/hd) (host copy of the workspace's table)
     Tuning tn;                    // launch-shape overrides, read from the environment once by d3_create
     bool prefill_by_seq;          // prompt pass one sequence at a time (D3_PREFILL_BY_SEQ, default on)
     int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU; default 2, 1 for grouped-query models)
@@ -189,6 +205,13 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     D3_HIP(hipGetDeviceProperties(&prop, dev));
     if (strncmp(prop.gcnArchName, "gfx950", 6) != 0) return fail(D3_EDEVICE, "d3_create: built for gfx950, device is %s", prop.gcnArchName);
 
+    if (dev < 0 || dev >= kMaxDevices) return fail(D3_EDEVICE, "d3_create: device index %d is outside [0, %d)", dev, kMaxDevices);
+    if (!g_scratch_ptr[dev].load(std::memory_order_acquire)) {   // this GPU's copy of the static scratch array (the device is current)
+        void* p = nullptr;
+        D3_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+
     d3_ctx* c = new (std::nothrow) d3_ctx();
     if (!c) return fail(D3_EINVAL, "d3_create: out of host memory");
     c->desc = *desc;
@@ -197,6 +220,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->k_cache = static_cast<char*>(k_cache); c->v_cache = static_cast<char*>(v_cache); c->ws = static_cast<char*>(workspace);
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
+    c->dev = dev;
     c->gemv_wgs_per_cu = 3;
     c->tn = tuning_from_env();
     // grouped-query models on the MFMA attention kernel (fp16 cache, head_dim 128, 4 or 8 heads per KV head) do better with
@@ -218,7 +242,8 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->row_n_drop.assign(desc->max_seq, 0);
 
     // rotary frequencies base^(-2j/hd), in binary64
-    std::vector<double> inv(desc->head_dim / 2);
+    std::vector<double>& inv = c->inv_freq;
+    inv.resize(desc->head_dim / 2);
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kPassCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
@@ -586,8 +611,10 @@ extern "C" int d3_prefill_ragged(d3_ctx* ctx, const int32_t* tokens, const int32
     return prefill_impl(ctx, tokens, B, P, 0, lengths, next_tok, logits, hidden_dump, hip_stream);
 }
 
-extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits,
-                              float* hidden_dump, void* hip_stream) {
+namespace {
+
+int decode_step_impl(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits, float* hidden_dump,
+                     hipStream_t s, bool static_scratch) {
     if (!ctx || !tok_in || !tok_out) return fail(D3_EINVAL, "d3_decode_step: NULL argument");
     if (!ctx->has_plan) return fail(D3_ESTATE, "d3_decode_step: no plan set (call d3_set_plan)");
     if (!ctx->prefilled) return fail(D3_ESTATE, "d3_decode_step: no prompt pass yet (call d3_prefill)");
@@ -596,11 +623,36 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     if (ctx->n_ctx >= ctx->desc.max_seq) return fail(D3_ERANGE, "d3_decode_step: cache is full (%d rows)", ctx->n_ctx);
     const int L = ctx->desc.n_layers, B = ctx->B;
     const int kept = ctx->keep[step_i];
+    char* const own_ws = ctx->ws;
+    const Layout own_lay = ctx->lay;
+    if (static_scratch) {
+        // the step's buffers, laid out for max_batch columns, inside this GPU's static array; the few words of state the
+        // workspace carries between calls (rotary frequencies, first rows of a ragged batch, zeroed arrival counters) are
+        // written there by one small kernel first, because the array keeps whatever the last call on this GPU left
+        if (ctx->fill_mode == D3_FILL_RECOMPUTE)
+            return fail(D3_ESTATE, "d3_decode_step_static: the RECOMPUTE fill keeps a residual in the context's workspace; use d3_decode_step");
+        const Layout sl = make_layout(ctx->desc, ctx->desc.max_batch, kMaxCols, ctx->desc.max_batch > 16);
+        if (sl.total > kStaticScratchBytes)
+            return fail(D3_ESHAPE, "d3_decode_step_static: a step of this model at max_batch %d needs %zu bytes of scratch, the static array holds %zu",
+                        ctx->desc.max_batch, sl.total, kStaticScratchBytes);
+        char* sp = static_cast<char*>(g_scratch_ptr[ctx->dev].load(std::memory_order_acquire));
+        if (!sp) return fail(D3_ESTATE, "d3_decode_step_static: no static scratch on device %d", ctx->dev);
+        StaticSeed seed{};
+        for (size_t j = 0; j < ctx->inv_freq.size(); ++j) seed.inv_freq[j] = ctx->inv_freq[j];
+        for (int b = 0; b < kMaxCols; ++b) seed.row0[b] = ctx->row0[b];
+        D3_HIP(launch_static_seed(seed, reinterpret_cast<double*>(sp + sl.inv_freq), ctx->desc.head_dim / 2, reinterpret_cast<int*>(sp + sl.row0),
+                                  reinterpret_cast<int*>(sp + sl.tickets), ctx->desc.max_batch * ctx->desc.n_heads,
+                                  reinterpret_cast<int*>(sp + sl.gemm_tickets), kGemmPartTickets, s));
+        ctx->ws = sp;
+        ctx->lay = sl;
+    }
     ColMap cm{0, B, 1, ctx->n_ctx};
     HeadOut head{0, B, logits ? logits : ctx->at<float>(ctx->lay.logits), tok_out};
     const bool keep_skip = ctx->fill_mode == D3_FILL_RECOMPUTE && kept < L;
-    const int rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head,
-                           static_cast<hipStream_t>(hip_stream), keep_skip ? ctx->drop_begin[step_i] + (L - kept) : -1);
+    const int rc = forward(ctx, tok_in, cm, B, ctx->layer_ids.data() + (size_t)step_i * L, kept, hidden_dump, 0, B, &head, s,
+                           keep_skip ? ctx->drop_begin[step_i] + (L - kept) : -1);
+    ctx->ws = own_ws;
+    ctx->lay = own_lay;
     ctx->skip_row = keep_skip && rc == D3_OK ? ctx->n_ctx : -1;
     if (rc != D3_OK) return rc;
     ctx->row_drop_begin[ctx->n_ctx] = ctx->drop_begin[step_i];
@@ -609,6 +661,20 @@ extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i
     ctx->last_step = step_i;
     return D3_OK;
 }
+
+}  // namespace
+
+extern "C" int d3_decode_step(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits,
+                              float* hidden_dump, void* hip_stream) {
+    return decode_step_impl(ctx, tok_in, step_i, tok_out, logits, hidden_dump, static_cast<hipStream_t>(hip_stream), false);
+}
+
+extern "C" int d3_decode_step_static(d3_ctx* ctx, const int32_t* tok_in, int32_t step_i, int32_t* tok_out, float* logits,
+                                     float* hidden_dump, void* hip_stream) {
+    return decode_step_impl(ctx, tok_in, step_i, tok_out, logits, hidden_dump, static_cast<hipStream_t>(hip_stream), true);
+}
+
+extern "C" size_t d3_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
 // RECOMPUTE fill of the row the latest decode step wrote: every dropped block l gets
 // K[l][p] = RoPE(W_k^l a), V[l][p] = W_v^l a with a = RMSNorm_l(h), h = the residual that entered the drop window

@@ -185,4 +185,13 @@ struct FillArgs {
 };
 int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s);
 
+// The words of state a decode step expects in its scratch area, passed by value (no host buffer to copy from) and
+// written by one small kernel, which also zeroes the arrival counters.
+struct StaticSeed {
+    double inv_freq[64];   // head_dim / 2 <= 64 rotary frequencies
+    int row0[kMaxCols];    // first cache row of each sequence (all zero unless the batch is left-padded)
+};
+int launch_static_seed(const StaticSeed& seed, double* inv_freq, int half_hd, int* row0, int* tickets, int n_tickets,
+                       int* gemm_tickets, int n_gemm_tickets, hipStream_t s);
+
 }  // namespace d3

@@ -181,7 +181,25 @@ __global__ __launch_bounds__(64) void fill_kernel(FillArgs a, int bytes_per_vec)
     }
 }
 
+// ---------------- state words of a decode step that runs in the static scratch array ----------------
+__global__ __launch_bounds__(256) void static_seed_kernel(StaticSeed seed, double* __restrict__ inv_freq, int half_hd, int* __restrict__ row0,
+                                                          int* __restrict__ tickets, int n_tickets, int* __restrict__ gemm_tickets,
+                                                          int n_gemm_tickets) {
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x, n = gridDim.x * blockDim.x;
+    if (tid < half_hd) inv_freq[tid] = seed.inv_freq[tid];
+    if (tid < kMaxCols) row0[tid] = seed.row0[tid];
+    for (int i = tid; i < n_tickets; i += n) tickets[i] = 0;
+    for (int i = tid; i < n_gemm_tickets; i += n) gemm_tickets[i] = 0;
+}
+
 }  // namespace
+
+int launch_static_seed(const StaticSeed& seed, double* inv_freq, int half_hd, int* row0, int* tickets, int n_tickets,
+                       int* gemm_tickets, int n_gemm_tickets, hipStream_t s) {
+    hipLaunchKernelGGL(static_seed_kernel, dim3(8), dim3(256), 0, s, seed, inv_freq, half_hd, row0, tickets, n_tickets, gemm_tickets,
+                       n_gemm_tickets);
+    return (int)hipGetLastError();
+}
 
 int launch_embed(const void* tok_emb, int weight_dtype, const int32_t* tokens, ColMap cm, int ncols, int d,
                  int vocab, float* x, const double* inv_freq, int half_hd, float2* rope_cs, const int* row0, hipStream_t s) {

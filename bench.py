@@ -12,7 +12,14 @@ untimed; each step rewinds the cache to the prompt with d3_truncate.  `value` is
 tokens/s at alpha = 0.995; full depth (alpha = 1) and alpha = 0.99 are reported beside it,
 each with its algorithmic HBM bytes per token and fraction of the 8 TB/s peak.
 
-python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny|7b-long] [--fill copy|recompute|none]
+Beside the headline the line carries: `kernels` (every kernel class of a block at full depth: microseconds per launch
+between HIP events on the launch stream, algorithmic bytes, fraction of the 8 TB/s peak), `roofline` (the dominant
+kernel, same clock), a read-only streaming yardstick (`stream_read`), the prompt pass against the bf16 matrix-core
+peak (`prefill`), and `by_config`: the 13B (batch 4), 7B batch-32 and 70B (batch 8) configurations, each with full
+depth and D^3, two timed requests each (skip them with --no-extra-configs).
+
+python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny|7b-long|7b-ragged]
+                [--fill copy|recompute|none] [--no-extra-configs] [--no-cpu-baseline] [--kv f16|f32]
 """
 from __future__ import annotations
 
@@ -30,6 +37,7 @@ sys.path.insert(0, ROOT)
 import d3_inputs  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 FILL_MODES = {}
 
 CONFIGS = {
@@ -71,6 +79,22 @@ def algorithmic_bytes(s, B, P, G, keep, kv_bytes_per_elem, fill="copy", prompt_r
     return total
 
 
+def kernel_bytes(s, B, P, G, kv_bytes_per_elem):
+    """Algorithmic bytes one launch of each kernel class moves at batch B (weights once, activations in and out;
+    attention: the K and V rows of B sequences averaged over the request's steps, q in, output out)."""
+    wb = 4 if s.dtype == "f32" else 2
+    qdim, kvdim = s.H * s.hd, s.H_kv * s.hd
+    kv_row = 2 * kvdim * kv_bytes_per_elem
+    return {
+        "qkv": (qdim + 2 * kvdim) * s.d * wb + B * s.d * 4 + B * (qdim + 2 * kvdim) * 4,
+        "attn": sum(B * (P + i) * kv_row for i in range(1, G)) / (G - 1) + 2 * B * qdim * 4,
+        "o": s.d * qdim * wb + B * qdim * 4 + 2 * B * s.d * 4,
+        "gate_up": 2 * s.F * s.d * wb + B * s.d * 4 + B * s.F * 4,
+        "down": s.d * s.F * wb + B * s.F * 4 + 2 * B * s.d * 4,
+        "lm_head": s.V * s.d * wb + B * s.d * 4 + B * s.V * 4,
+    }
+
+
 def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy", table=None):
     """`requests` whole generation phases back to back; returns seconds (host clock around a device sync).
     table: (keep, drop_begin) of a schedule to follow instead of the power law."""
@@ -83,7 +107,7 @@ def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy",
         if table is not None:
             dec.set_plan_table(table[0], table[1])
         else:
-            dec.set_plan(alpha, start, 0, G)
+            dec.set_plan(alpha, start, 0, G)          # host only: the schedule of the request
         cur.copy_(first_tok)
         for i in range(1, G):
             dec.decode_step(cur, i, nxt)
@@ -94,11 +118,164 @@ def run_decode(dec, torch, first_tok, P, G, alpha, start, requests, fill="copy",
     return time.perf_counter() - t0
 
 
+def yardsticks(dec, torch, dev):
+    """A plain 1 GiB device-to-device copy (read + written bytes per second; it also scales the FETCH_SIZE / WRITE_SIZE
+    counters when this command runs under rocprofv3 --pmc) and a read-only stream over 2 GiB with the projections' own
+    load instructions and launch shape: what the memory system gives a kernel that only reads."""
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        cal_dst.copy_(cal_src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del cal_dst
+    big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
+    big.zero_()
+    out = {}
+    for name, t in (("2 GiB", big), ("1 GiB", cal_src), ("128 MiB", cal_src[: 128 << 20])):
+        dec.stream_read(t)
+        torch.cuda.synchronize()
+        n = 5 if t.numel() >= (1 << 30) else 40
+        ev0.record()
+        for _ in range(n):
+            dec.stream_read(t)
+        ev1.record()
+        torch.cuda.synchronize()
+        out[name] = n * t.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del big, cal_src
+    return copy_gbps, out
+
+
+def progress(msg):
+    """Progress lines go to stderr (stdout carries the one JSON line); a long run must not stay silent."""
+    print("bench: " + msg, file=sys.stderr, flush=True)
+
+
+def measure_config(name, steps, warmup, fill, kv_arg=None, with_yardsticks=False, compare_schedules=False):
+    """Everything measured for one configuration; frees its device memory before returning."""
+    import torch
+    from paper_2503_08524_amd import binding
+    shape, B, P, G, alphas, start_frac = CONFIGS[name]
+    start = d3_inputs.start_layer_from_fraction(shape.L, start_frac)
+    dev = "cuda:0"
+    kv = kv_arg or binding.default_kv_dtype(shape)
+    progress(f"{name}: drawing weights on the device")
+    weights = binding.random_weights_on_device(shape, 0, dev)
+    dec = binding.Decoder(shape, weights, B, P + G, kv_dtype=kv, device=dev)
+    prompts = torch.from_numpy(d3_inputs.make_prompt(B, P, shape.V, seed=1)).to(dev)
+    res = {"kv_cache": kv}
+    if with_yardsticks:
+        res["stream_copy_GBps"], res["stream_read_GBps"] = yardsticks(dec, torch, dev)
+
+    dec.set_plan(alphas[0], start, 0, G)
+    if fill == "recompute":
+        dec.set_fill_mode(binding.D3_FILL_RECOMPUTE)
+    lengths = RAGGED_LENGTHS.get(name)
+    prompt_rows = sum(lengths) if lengths else None
+    prefill = (lambda: dec.prefill_ragged(prompts, lengths)) if lengths else (lambda: dec.prefill(prompts))
+    progress(f"{name}: prompt pass, {prompt_rows or B * P} tokens (twice: the first pages the kernels in)")
+    first_tok = prefill()                      # first pass also pages the kernels in
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    first_tok = prefill()
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    n_prompt = prompt_rows or B * P
+    # matrix-core work of the prompt pass: 2 flops per weight per token (lm_head once per sequence) plus the causal
+    # attention contractions; the kernels issue twice that (activations go in as bf16 hi + lo)
+    attn_flops = sum(4 * shape.H * shape.hd * (p + 1) for p in range(P)) * B * shape.L if not lengths else 0
+    flops = 2.0 * shape.params_per_block * shape.L * n_prompt + 2.0 * shape.V * shape.d * B + attn_flops
+    res["prefill"] = {"tokens": n_prompt, "seconds": prefill_s, "tokens_per_s": n_prompt / prefill_s,
+                      "algorithmic_TFLOPs": flops / prefill_s / 1e12, "issued_TFLOPs_hi_lo": 2 * flops / prefill_s / 1e12,
+                      "bound": "mfma", "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS,
+                      "frac_algorithmic": flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                      "frac_issued": 2 * flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+
+    kv_bytes = 4 if kv == "f32" else 2
+    results = {}
+    for alpha in alphas:
+        keep, _, _ = binding.d3_plan_depth(shape.L, alpha, start, 0, G)
+        run_decode(dec, torch, first_tok, P, G, alpha, start, warmup, fill)
+        secs = run_decode(dec, torch, first_tok, P, G, alpha, start, steps, fill)
+        n_tok = steps * (G - 1) * B
+        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes, fill, prompt_rows) * steps
+        progress(f"{name}: alpha {alpha}: {n_tok / secs:.1f} tokens/s, {secs / (steps * (G - 1)) * 1e3:.3f} ms per decode step")
+        results[alpha] = {
+            "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (steps * (G - 1)) * 1e3,
+            "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (steps * (G - 1)) / 1e9,
+            "achieved_GBps": alg / secs / 1e9, "frac_of_hbm_peak": alg / secs / 1e9 / HBM_PEAK_GBPS,
+        }
+    if 1.0 in results:
+        for a, r in results.items():
+            r["speedup_vs_full_depth"] = r["tokens_per_s"] / results[1.0]["tokens_per_s"]
+            r["ideal_layer_count_ratio"] = shape.L / r["avg_blocks"]
+            r["ideal_byte_ratio"] = results[1.0]["algorithmic_GB_per_token_step"] / r["algorithmic_GB_per_token_step"]
+    res["by_alpha"] = {str(a): r for a, r in results.items()}
+
+    if compare_schedules and 1.0 in results:
+        # Same kernels, other plans (Section 4.1's comparison methods as far as the paper defines them: which blocks go
+        # first, and linear instead of power-law decay between bounds chosen to give at least the same average depth).
+        L = shape.L
+        d3_keep, d3_drop, _ = binding.d3_plan_depth(L, alphas[0], start, 0, G)
+        avg = float(d3_keep[1:G].mean())
+        last = max(0, min(L, int(2 * avg - L)))
+        while last < L and float(binding.d3_plan_depth_linear(L, L, last, 0, G)[0][1:G].mean()) < avg:
+            last += 1
+        plans = {"power law, middle blocks first (D^3)": (d3_keep, d3_drop),
+                 "power law, deep blocks first (early exit)": binding.d3_plan_depth(L, alphas[0], L - 1, 0, G)[:2],
+                 "linear %d -> %d, shallow blocks first" % (L, last): binding.d3_plan_depth_linear(L, L, last, 0, G)[:2]}
+        schedules = {}
+        for pname, table in plans.items():
+            run_decode(dec, torch, first_tok, P, G, 1.0, start, warmup, fill, table=table)
+            secs = run_decode(dec, torch, first_tok, P, G, 1.0, start, steps, fill, table=table)
+            k = table[0]
+            schedules[pname] = {"avg_blocks": float(k[1:G].mean()), "tokens_per_s": steps * (G - 1) * B / secs,
+                                "speedup_vs_full_depth": steps * (G - 1) * B / secs / results[1.0]["tokens_per_s"],
+                                "ideal_layer_count_ratio": L / float(k[1:G].mean())}
+        res["schedules"] = schedules
+
+    # every kernel class of a block, each launch bracketed by two HIP events on the launch stream, over one more
+    # full-depth request per class; the empty bracket (no launch inside) is what the event pair itself adds
+    kb = kernel_bytes(shape, B, P, G, kv_bytes)
+    classes = {"qkv": binding.D3_K_QKV, "attn": binding.D3_K_ATTN, "o": binding.D3_K_OPROJ, "gate_up": binding.D3_K_GATE_UP,
+               "down": binding.D3_K_DOWN, "lm_head": binding.D3_K_LM_HEAD, "empty_bracket": binding.D3_K_EMPTY}
+    kernels = {}
+    for cname, cls in classes.items():
+        dec.profile_select(cls)
+        run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, "none")
+        ms, n = dec.profile_read()
+        us = ms / n * 1e3 if n else None
+        kernels[cname] = {"us_per_launch": us, "launches": n}
+        progress(f"{name}: kernel class {cname}: {us if us is None else round(us, 2)} us per launch")
+    dec.profile_select(binding.D3_K_NONE)
+    pair_us = kernels["empty_bracket"]["us_per_launch"] or 0.0
+    for cname, k in kernels.items():
+        if cname == "empty_bracket" or not k["launches"]:
+            continue
+        k["bytes_per_launch"] = kb[cname]
+        k["GBps"] = kb[cname] / (k["us_per_launch"] * 1e-6) / 1e9
+        k["frac_of_hbm_peak"] = k["GBps"] / HBM_PEAK_GBPS
+        k["us_minus_event_pair"] = k["us_per_launch"] - pair_us
+        k["frac_minus_event_pair"] = kb[cname] / (k["us_minus_event_pair"] * 1e-6) / 1e9 / HBM_PEAK_GBPS
+    res["kernels"] = kernels
+    res["dominant"] = "attn" if name == "7b-b32" else "gate_up"
+    dec.close()
+    del dec, weights, prompts, first_tok
+    torch.cuda.empty_cache()
+    return res
+
+
 def cpu_baseline(shape, keep_mean):
     """The oracle (float32 build, one thread) on a one-block model of the same widths; per-block and
     lm_head times extrapolated to the workload's average depth."""
     from oracle import oracle
     s1 = shape.truncated(1)
+    progress("cpu_baseline: drawing one block on the host")
     w = d3_inputs.make_weights(s1, 0)
     model = oracle.OracleModel(s1, w, "f32")
     oracle.set_threads(1, "f32")
@@ -128,7 +305,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="7b", choices=sorted(CONFIGS))
+    ap.add_argument("--kv", default=None, choices=["f16", "f32"], help="KV cache precision (default: by model depth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra-configs", action="store_true", help="skip the by_config entries (13b, 7b-b32, 70b)")
     ap.add_argument("--no-fill", action="store_true", help="same as --fill none")
     ap.add_argument("--fill", default="copy", choices=["copy", "recompute", "none"],
                     help="missing-state fill after every decode step (Section 3.2): KV copy (default), KV recompute, or none")
@@ -144,110 +323,24 @@ def main() -> int:
     from paper_2503_08524_amd import binding
     FILL_MODES.update(copy=binding.D3_FILL_COPY, recompute=binding.D3_FILL_RECOMPUTE)
     fill = "none" if args.no_fill else args.fill
+    torch.cuda.set_device(0)
 
     shape, B, P, G, alphas, start_frac = CONFIGS[args.config]
     start = d3_inputs.start_layer_from_fraction(shape.L, start_frac)
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    kv = "f32" if shape.dtype == "f32" else "f16"
-    weights = binding.random_weights_on_device(shape, 0, dev)
-    dec = binding.Decoder(shape, weights, B, P + G, kv_dtype=kv, device=dev)
-    prompts = torch.from_numpy(d3_inputs.make_prompt(B, P, shape.V, seed=1)).to(dev)
-
-    # a plain device-to-device copy of known size (1 GiB read + 1 GiB written): the yardstick that scales the
-    # FETCH_SIZE / WRITE_SIZE counters when this command runs under rocprofv3 --pmc
-    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cal_dst = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cal_dst.copy_(cal_src)
-    torch.cuda.synchronize()
-    # the same copy, timed: what a plain streaming kernel reaches on this chip (bytes read + bytes written per second),
-    # the ceiling that the fractions of the nominal 8 TB/s can be held against
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for _ in range(5):
-        cal_dst.copy_(cal_src)
-    ev1.record()
-    torch.cuda.synchronize()
-    copy_gbps = 5 * 2 * (1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
-    del cal_src, cal_dst
-
-    dec.set_plan(alphas[0], start, 0, G)
-    if fill == "recompute":
-        dec.set_fill_mode(binding.D3_FILL_RECOMPUTE)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
     lengths = RAGGED_LENGTHS.get(args.config)
-    first_tok = dec.prefill_ragged(prompts, lengths) if lengths else dec.prefill(prompts)
-    prompt_rows = sum(lengths) if lengths else None
-    torch.cuda.synchronize()
-    prefill_s = time.perf_counter() - t0
-
-    kv_bytes = 4 if kv == "f32" else 2
-    results = {}
-    for alpha in alphas:
-        keep, _, _ = binding.d3_plan_depth(shape.L, alpha, start, 0, G)
-        run_decode(dec, torch, first_tok, P, G, alpha, start, args.warmup, fill)
-        secs = run_decode(dec, torch, first_tok, P, G, alpha, start, args.steps, fill)
-        n_tok = args.steps * (G - 1) * B
-        alg = algorithmic_bytes(shape, B, P, G, keep, kv_bytes, fill, prompt_rows) * args.steps
-        results[alpha] = {
-            "tokens_per_s": n_tok / secs, "ms_per_token_step": secs / (args.steps * (G - 1)) * 1e3,
-            "avg_blocks": float(keep[1:G].mean()), "algorithmic_GB_per_token_step": alg / (args.steps * (G - 1)) / 1e9,
-            "achieved_GBps": alg / secs / 1e9, "frac_of_hbm_peak": alg / secs / 1e9 / HBM_PEAK_GBPS,
-            "frac_of_measured_copy_rate": alg / secs / 1e9 / copy_gbps,
-        }
-    head = results[alphas[0]]
-    if 1.0 in results:
-        for a, r in results.items():
-            r["speedup_vs_full_depth"] = r["tokens_per_s"] / results[1.0]["tokens_per_s"]
-            r["ideal_layer_count_ratio"] = shape.L / r["avg_blocks"]
-            r["ideal_byte_ratio"] = results[1.0]["algorithmic_GB_per_token_step"] / r["algorithmic_GB_per_token_step"]
-
-    schedules = None
-    if args.compare_schedules and 1.0 in results:
-        # Same kernels, other plans (Section 4.1's comparison methods as far as the paper defines them: which blocks go
-        # first, and linear instead of power-law decay between bounds chosen to give at least the same average depth).
-        L = shape.L
-        d3_keep, d3_drop, _ = binding.d3_plan_depth(L, alphas[0], start, 0, G)
-        avg = float(d3_keep[1:G].mean())
-        last = max(0, min(L, int(2 * avg - L)))
-        while last < L and float(binding.d3_plan_depth_linear(L, L, last, 0, G)[0][1:G].mean()) < avg:
-            last += 1
-        plans = {"power law, middle blocks first (D^3)": (d3_keep, d3_drop),
-                 "power law, deep blocks first (early exit)": binding.d3_plan_depth(L, alphas[0], L - 1, 0, G)[:2],
-                 "linear %d -> %d, shallow blocks first" % (L, last): binding.d3_plan_depth_linear(L, L, last, 0, G)[:2]}
-        schedules = {}
-        for name, table in plans.items():
-            run_decode(dec, torch, first_tok, P, G, 1.0, start, args.warmup, fill, table=table)
-            secs = run_decode(dec, torch, first_tok, P, G, 1.0, start, args.steps, fill, table=table)
-            k = table[0]
-            schedules[name] = {"avg_blocks": float(k[1:G].mean()), "tokens_per_s": args.steps * (G - 1) * B / secs,
-                               "speedup_vs_full_depth": args.steps * (G - 1) * B / secs / results[1.0]["tokens_per_s"],
-                               "ideal_layer_count_ratio": L / float(k[1:G].mean())}
-
-    # dominant kernel, every launch bracketed by HIP events on the launch stream, over one more full-depth request
-    wbytes = 4 if shape.dtype == "f32" else 2
-    if args.config == "7b-b32":
-        # at batch 32 the cache rows outweigh the weights: attention is the dominant kernel (one launch per block;
-        # bytes averaged over the request's steps: K and V rows of B sequences, read once)
-        kernel = "decode attention (RoPE + KV append + split merge included)"
-        kv_row = 2 * shape.H_kv * shape.hd * kv_bytes
-        kclass, bytes_per_launch = binding.D3_K_ATTN, sum(B * (P + i) * kv_row for i in range(1, G)) / (G - 1) + 2 * B * shape.d * 4
-    else:
-        kernel = "fused RMSNorm + gate/up + SiLU*mul projection"
-        kclass, bytes_per_launch = binding.D3_K_GATE_UP, 2 * shape.F * shape.d * wbytes + B * shape.d * 4 + B * shape.F * 4
-    dec.profile_select(kclass)
-    run_decode(dec, torch, first_tok, P, G, 1.0, start, 1, "none")
-    ms, n = dec.profile_read()
-    dec.profile_select(binding.D3_K_NONE)
-    achieved = bytes_per_launch / (ms / n * 1e-3) / 1e9 if n else 0.0
-    # HBM bytes per launch of that kernel from the committed rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE,
-    # each scaled by what a plain 1 GiB copy reads on the same counter); only known for the profiled workload
-    traffic = None
-    profiled = {"7b": ("decode_7b_b1", "gemv_alu_kernel<unsigned short, 1, 2, true>"),       # gate/up kernel of each configuration
+    m = measure_config(args.config, args.steps, args.warmup, fill, args.kv, with_yardsticks=True,
+                       compare_schedules=args.compare_schedules)
+    head = m["by_alpha"][str(alphas[0])]
+    dom = m["kernels"][m["dominant"]]
+    kernel_names = {"gate_up": "fused RMSNorm + gate/up + SiLU*mul projection",
+                    "attn": "decode attention (RoPE + KV append + split merge included)"}
+    # HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc runs of this command (FETCH_SIZE +
+    # WRITE_SIZE, each scaled by what a plain 1 GiB copy reads on the same counter); only known for a profiled workload
+    traffic, traffic_source = None, None
+    profiled = {"7b": ("decode_7b_b1", "gemv_alu_kernel<unsigned short, 1, 2, true>"),
                 "13b": ("decode_13b_b4", "gemm_mfma_kernel<1, 2, 2, true>"),
                 "70b": ("decode_70b_b8", "gemm_mfma_kernel<1, 2, 1, true>")}
-    if args.config in profiled and kclass == binding.D3_K_GATE_UP:
+    if args.config in profiled and m["dominant"] == "gate_up":
         stem, kname = profiled[args.config]
         tpath = os.path.join(ROOT, "profiles", stem + "_hbm_traffic.json")
         if os.path.exists(tpath):
@@ -255,27 +348,55 @@ def main() -> int:
                 ks = [v for name, v in json.load(f)["kernels"].items() if kname in name]
             if ks and ks[0]["write_bytes_per_launch"] is not None:
                 traffic = ks[0]["fetch_bytes_per_launch"] + ks[0]["write_bytes_per_launch"]
-    roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved,
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                "launches_timed": n, "avg_launch_us": ms / n * 1e3 if n else None, "bytes_per_launch": bytes_per_launch}
+                traffic_source = "profiles/%s_hbm_traffic.json (committed rocprofv3 --pmc runs of this command, not this run)" % stem
+    roofline = {"bound": "hbm", "kernel": kernel_names[m["dominant"]], "achieved": dom["GBps"], "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": dom["frac_of_hbm_peak"], "traffic": traffic, "traffic_source": traffic_source,
+                "clock": "HIP events recorded on the launch stream around every launch of the kernel (full-depth request); "
+                         "the pair of events adds kernels.empty_bracket.us_per_launch to each, which the kernel trace in profiles/ "
+                         "does not see: frac_minus_event_pair is the same figure without it",
+                "launches_timed": dom["launches"], "avg_launch_us": dom["us_per_launch"],
+                "avg_launch_us_minus_event_pair": dom["us_minus_event_pair"], "frac_minus_event_pair": dom["frac_minus_event_pair"],
+                "bytes_per_launch": dom["bytes_per_launch"]}
+    copy_gbps = m["stream_copy_GBps"]
+    for r in m["by_alpha"].values():
+        r["frac_of_measured_read_rate"] = r["achieved_GBps"] / m["stream_read_GBps"]["2 GiB"]
 
     out = {
         "metric": "decode tokens/sec (D^3, alpha=%g) at the Llama-7B shape; achieved HBM GB/s beside it" % alphas[0]
         if args.config == "7b" else "decode tokens/sec (D^3, alpha=%g)" % alphas[0],
         "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_token_step"] * (G - 1), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32" if shape.dtype == "f32" else "bf16 weights, f32 accumulate, f16 KV cache",
+        "vs_baseline": None,
+        "dtype": "f32" if shape.dtype == "f32" else "bf16 weights, f32 accumulate, %s KV cache" % m["kv_cache"],
         "data": "synthetic",
         "config": {"workload": f"{shape.name} B={B} P={P if not lengths else list(lengths)} G={G} alpha={alphas[0]} start_layer={start}",
-                   "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": kv,
+                   "step": f"one request's generation phase = {G - 1} decode steps", "kv_cache": m["kv_cache"],
                    "fill_every_step": fill},
-        "ms_per_token": head["ms_per_token_step"], "prefill_s": prefill_s,
-        "by_alpha": {str(a): r for a, r in results.items()},
+        "ms_per_token": head["ms_per_token_step"], "prefill_s": m["prefill"]["seconds"], "prefill": m["prefill"],
+        "by_alpha": m["by_alpha"],
         "stream_copy": {"GBps": copy_gbps, "what": "1 GiB device-to-device copy, read + written bytes per second (5 repeats)"},
+        "stream_read": {"GBps": m["stream_read_GBps"],
+                        "what": "read-only stream with the projections' load instructions and launch shape (d3_stream_read), "
+                                "bytes read per second by buffer size"},
         "roofline": roofline,
+        "kernels": m["kernels"],
     }
-    if schedules is not None:
-        out["schedules"] = schedules
+    if "schedules" in m:
+        out["schedules"] = m["schedules"]
+    if not args.no_extra_configs and args.config == "7b":
+        # the other benchmark configurations, two timed requests each after one warm-up request
+        by_config = {}
+        for name in ("13b", "7b-b32", "70b"):
+            e = measure_config(name, 2, 1, fill)
+            s2, B2, P2, G2, al2, _ = CONFIGS[name]
+            d2 = e["kernels"][e["dominant"]]
+            by_config[name] = {"workload": f"{s2.name} B={B2} P={P2} G={G2}", "kv_cache": e["kv_cache"], "timed_requests": 2,
+                               "by_alpha": e["by_alpha"], "prefill": e["prefill"],
+                               "dominant_kernel": {"class": e["dominant"], "us_per_launch": d2["us_per_launch"],
+                                                   "bytes_per_launch": d2["bytes_per_launch"], "frac_of_hbm_peak": d2["frac_of_hbm_peak"],
+                                                   "frac_minus_event_pair": d2["frac_minus_event_pair"]},
+                               "kernels": {k: {kk: v.get(kk) for kk in ("us_per_launch", "frac_of_hbm_peak")} for k, v in e["kernels"].items()}}
+        out["by_config"] = by_config
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(shape, head["avg_blocks"])
     print(json.dumps(out))

@@ -227,10 +227,18 @@ int d3_truncate(d3_ctx *ctx, int32_t n_rows);
  * recorded events, returns their summed duration and count, and clears them.
  * Selecting D3_K_NONE switches the bracketing off. */
 typedef enum {
-    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6
+    D3_K_NONE = 0, D3_K_QKV = 1, D3_K_ATTN = 2, D3_K_OPROJ = 3, D3_K_GATE_UP = 4, D3_K_DOWN = 5, D3_K_LM_HEAD = 6,
+    D3_K_EMPTY = 7 /* a bracket with no launch inside, recorded once per block between the gate/up and the down
+                      projection: what the pair of events itself adds to every bracketed launch */
 } d3_kernel_class;
 int d3_profile_select(d3_ctx *ctx, int32_t kernel_class);
 int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
+
+/* Measurement aid: one launch that reads `bytes` of device memory (16-byte aligned, a multiple of 16) exactly once
+ * and writes nothing but a checksum, with the same load instructions and launch shape as the weight-streaming
+ * projections (Section 4.2 measures wall-clock time; this is the read-only yardstick the achieved HBM rates are held
+ * against).  Asynchronous on the given stream; the checksum lands in the context's workspace. */
+int d3_stream_read(d3_ctx *ctx, const void *src, size_t bytes, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ _LIB: Optional[C.CDLL] = None
 D3_F32, D3_BF16, D3_F16 = 0, 1, 2
 D3_FILL_COPY = 0
 D3_FILL_RECOMPUTE = 1
-D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD = range(7)
+D3_K_NONE, D3_K_QKV, D3_K_ATTN, D3_K_OPROJ, D3_K_GATE_UP, D3_K_DOWN, D3_K_LM_HEAD, D3_K_EMPTY = range(8)
 
 
 class D3Error(RuntimeError):
@@ -75,6 +75,7 @@ def load_library() -> C.CDLL:
         lib.d3_n_ctx.argtypes = [vp]
         lib.d3_n_ctx.restype = i32
         lib.d3_truncate.argtypes = [vp, i32]
+        lib.d3_stream_read.argtypes = [vp, vp, C.c_size_t, vp]
         lib.d3_profile_select.argtypes = [vp, i32]
         lib.d3_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _LIB = lib
@@ -240,6 +241,10 @@ class Decoder:
 
     def truncate(self, n_rows: int) -> None:
         _check(self.lib.d3_truncate(self.ctx, n_rows))
+
+    def stream_read(self, tensor) -> None:
+        """Read-only streaming yardstick over a CUDA tensor (one launch, asynchronous)."""
+        _check(self.lib.d3_stream_read(self.ctx, tensor.data_ptr(), tensor.numel() * tensor.element_size(), self._stream()))
 
     def profile_select(self, kernel_class: int) -> None:
         _check(self.lib.d3_profile_select(self.ctx, kernel_class))

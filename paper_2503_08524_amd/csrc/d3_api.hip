@@ -108,6 +108,7 @@ int env_int(const char* name, long lo, long hi, long dflt) {
 namespace d3 {
 Tuning tuning_from_env() {
     Tuning t;
+    t.gemv_wgs_per_cu = env_int("D3_GEMV_WGS_PER_CU", 1, 8, 3);
     t.mfma_rt = env_int("D3_MFMA_RT", 1, 4, 0);
     t.mfma_waves = env_int("D3_MFMA_WAVES", 1, 8, 0);
     t.mfma_wide = env_int("D3_MFMA_WIDE", 0, 1, 1) != 0;
@@ -143,7 +144,6 @@ struct d3_ctx {
     Tuning tn;                    // launch-shape overrides, read from the environment once by d3_create
     bool prefill_by_seq;          // prompt pass one sequence at a time (D3_PREFILL_BY_SEQ, default on)
     int attn_wgs_per_cu;          // attention workgroups per CU that the context splits aim for (D3_ATTN_WGS_PER_CU; default 2, 1 for grouped-query models)
-    int gemv_wgs_per_cu;          // workgroups per CU of the weight-streaming GEMV (D3_GEMV_WGS_PER_CU, default 3)
     bool mfma_ok, alu_ok;         // which projection paths the shapes fit
     // plan
     bool has_plan;
@@ -221,7 +221,6 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->lay = lay;
     c->n_cu = prop.multiProcessorCount;
     c->dev = dev;
-    c->gemv_wgs_per_cu = 3;
     c->tn = tuning_from_env();
     // grouped-query models on the MFMA attention kernel (fp16 cache, head_dim 128, 4 or 8 heads per KV head) do better with
     // one workgroup per CU (70B shape, batch 8: 24.41 against 24.55 ms a step), the others with two (13B, batch 4: 5.71 against 5.78)
@@ -229,7 +228,6 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
                           (desc->n_heads / desc->n_kv_heads == 4 || desc->n_heads / desc->n_kv_heads == 8)) ? 1 : 2;
     c->prefill_by_seq = env_int("D3_PREFILL_BY_SEQ", 0, 1, 1) != 0;
     c->attn_wgs_per_cu = env_int("D3_ATTN_WGS_PER_CU", 1, 16, c->attn_wgs_per_cu);
-    c->gemv_wgs_per_cu = env_int("D3_GEMV_WGS_PER_CU", 1, 8, c->gemv_wgs_per_cu);
     c->mfma_ok = mfma_fits(*desc);
     c->alu_ok = alu_fits(*desc);
     c->prof_class = D3_K_NONE; c->prof_used = 0;
@@ -343,15 +341,15 @@ void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split
 // ALU path: a projection takes as many columns per launch as its input fits in LDS
 int alu_projection(d3_ctx* c, GemvArgs g, int first, int count, int mode, bool norm, hipStream_t s) {
     const int per = (int)gemv_alu_max_cols(g.K, c->desc.weight_dtype);
-    const int n_wg = c->n_cu * c->gemv_wgs_per_cu;
     for (int c0 = 0; c0 < count; c0 += per) {
         GemvArgs h = g;
         h.x = g.x + (size_t)(first + c0) * g.x_stride;
         h.out = g.out + (size_t)(first + c0) * g.out_stride;
         h.ncols = count - c0 < per ? count - c0 : per;
         h.col0 = first + c0;
-        int rc = launch_gemv_alu(h, c->desc.weight_dtype, mode, norm, n_wg, s);
+        int rc = launch_gemv_alu(h, c->desc.weight_dtype, mode, norm, c->n_cu * c->tn.gemv_wgs_per_cu, s);
         if (rc != 0) return rc;
+
     }
     return 0;
 }
@@ -372,10 +370,11 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
     bf16_t *s_hi = c->at<bf16_t>(c->lay.s_hi), *s_lo = c->at<bf16_t>(c->lay.s_lo);
     bf16_t *f_hi = c->at<bf16_t>(c->lay.f_hi), *f_lo = c->at<bf16_t>(c->lay.f_lo);
     const bool mfma = c->mfma_ok && (ncols >= 2 || !c->alu_ok);
-    // a decode pass (every column a different sequence) on the matrix-core path leaves the rotary embedding and the
-    // cache append to the attention kernel; a prompt chunk holds several positions of one sequence and needs the
-    // rows in the cache before attention starts
-    const bool rope_in_attn = mfma && ncols <= cm.B;
+    // a decode pass (every column a different sequence) leaves the rotary embedding and the cache append to the
+    // attention kernel (batch 1, 7B shape: the projection's rotate-and-scatter epilogue cost it 1.5 us, the attention
+    // kernel does the same for 0.5 us with whole-row stores); a prompt chunk holds several positions of one sequence
+    // and needs the rows in the cache before attention starts
+    const bool rope_in_attn = ncols <= cm.B;
 
     float2* rope_cs = c->at<float2>(c->lay.rope_cs);
     const int* row0 = c->ragged ? c->at<int>(c->lay.row0) : nullptr;
@@ -439,12 +438,12 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
                 D3_HIP(launch_rope_append(r, d.kv_dtype, s));
             }
         } else {
-            // the GEMV epilogue rotates q and k and appends the new K/V row itself
+            // a prompt chunk on this path: the GEMV epilogue rotates q and k and appends the new K/V rows itself
             g.x = x; g.x_stride = dm; g.gain = static_cast<const float*>(w.attn_norm);
             g.rope_cs = rope_cs; g.k_cache = k_layer; g.v_cache = v_layer; g.cm = cm;
             g.H = d.n_heads; g.H_kv = d.n_kv_heads; g.hd = hd; g.max_seq = d.max_seq; g.kv_dtype = d.kv_dtype;
             Timed t(c, D3_K_QKV, s);
-            D3_HIP(alu(g, 0, ncols, MODE_QKV_ROPE, true));
+            D3_HIP(alu(g, 0, ncols, rope_in_attn ? MODE_STORE : MODE_QKV_ROPE, true));
         }
         AttnArgs at{};
         at.q = qkv; at.q_stride = qkv_dim; at.k_cache = k_layer; at.v_cache = v_layer; at.cm = cm;
@@ -487,11 +486,13 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
             { Timed t(c, D3_K_GATE_UP, s); D3_HIP(launch_gemm_mfma(u, MODE_SWIGLU, c->n_cu, c->tn, s)); }
             dn.x_hi = f_hi; dn.x_lo = f_lo; dn.x_stride = F;
             dn.out_hi = n_hi; dn.out_lo = n_lo; dn.gain_next = gain_after(e); dn.ssq_out = ssq;
+            { Timed t(c, D3_K_EMPTY, s); }
             { Timed t(c, D3_K_DOWN, s); D3_HIP(launch_gemm_mfma(dn, MODE_RESID, c->n_cu, c->tn, s, &ssq_parts)); }
         } else {
             u.x = x; u.x_stride = dm; u.gain = static_cast<const float*>(w.mlp_norm); u.out = act;
             { Timed t(c, D3_K_GATE_UP, s); D3_HIP(alu(u, 0, ncols, MODE_SWIGLU, true)); }
             dn.x = act; dn.x_stride = F;
+            { Timed t(c, D3_K_EMPTY, s); }
             { Timed t(c, D3_K_DOWN, s); D3_HIP(alu(dn, 0, ncols, MODE_RESID, false)); }
         }
         D3_HIP(dump(e + 1));
@@ -773,9 +774,18 @@ extern "C" int d3_truncate(d3_ctx* ctx, int32_t n_rows) {
     return D3_OK;
 }
 
+extern "C" int d3_stream_read(d3_ctx* ctx, const void* src, size_t bytes, void* hip_stream) {
+    if (!ctx || !src) return fail(D3_EINVAL, "d3_stream_read: NULL argument");
+    if (bytes % 16 != 0 || reinterpret_cast<uintptr_t>(src) % 16 != 0) return fail(D3_EINVAL, "d3_stream_read: the buffer must be 16-byte aligned and a multiple of 16 bytes");
+    // three workgroups of four waves per compute unit, like the projections; their checksums land in the attention partials
+    const int n_wg = 3 * ctx->n_cu;
+    D3_HIP(launch_stream_read(src, bytes, ctx->at<unsigned>(ctx->lay.part_o), n_wg, static_cast<hipStream_t>(hip_stream)));
+    return D3_OK;
+}
+
 extern "C" int d3_profile_select(d3_ctx* ctx, int32_t kernel_class) {
     if (!ctx) return fail(D3_EINVAL, "d3_profile_select: ctx is NULL");
-    if (kernel_class < D3_K_NONE || kernel_class > D3_K_LM_HEAD) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
+    if (kernel_class < D3_K_NONE || kernel_class > D3_K_EMPTY) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);
     if (kernel_class != D3_K_NONE && ctx->prof_events.empty()) {
         ctx->prof_events.reserve(kMaxProfEvents);
         for (size_t i = 0; i < kMaxProfEvents; ++i) {

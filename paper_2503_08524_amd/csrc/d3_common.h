@@ -115,8 +115,10 @@ struct GemvArgs {
 // D3_MFMA_WIDE=0: no panel kernel (passes are limited to kMaxCols columns); D3_WIDE_RT, D3_WIDE_KS: row tiles per wave
 // and K slices of the panel kernel; D3_WIDE_SPLIT_MB: matrix size above which a pass of more than 64 columns runs as
 // two 64-column launches; D3_ATTN_MFMA=0: grouped-query and query-tile attention on the vector ALUs;
-// D3_ATTN_MIN_SPLIT: shortest context split; D3_PREFILL_COLS: 64 or 128 columns per prompt chunk.
+// D3_ATTN_MIN_SPLIT: shortest context split; D3_PREFILL_COLS: 64 or 128 columns per prompt chunk; D3_GEMV_WGS_PER_CU: workgroups
+// per compute unit of the vector-ALU GEMV (default 3).
 struct Tuning {
+    int gemv_wgs_per_cu = 3;
     int mfma_rt = 0, mfma_waves = 0;
     bool mfma_wide = true;
     int wide_rt = 0, wide_ks = 0;
@@ -184,6 +186,9 @@ struct FillArgs {
     int drop_begin, n_drop, src;   // src < 0: zero fill
 };
 int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s);
+
+// read-only streaming yardstick: reads `bytes` (a multiple of 16) once; sink: n_wg * 4 words
+int launch_stream_read(const void* src, size_t bytes, unsigned* sink, int n_wg, hipStream_t s);
 
 // The words of state a decode step expects in its scratch area, passed by value (no host buffer to copy from) and
 // written by one small kernel, which also zeroes the arrival counters.

@@ -1,5 +1,4 @@
-// Device-side phases of the vector-ALU GEMV (see gemv_alu.hip), kept as inline device
-// functions so that more than one kernel can be assembled from them.
+// Device-side phases of the vector-ALU GEMV (see gemv_alu.hip).
 //
 // A wave walks its work as a sequence of "steps": one step = the two weight rows of a unit
 // at one 64-lane stride (2 x 1 KiB per wave).  Loads run D steps ahead of the arithmetic in
@@ -126,26 +125,14 @@ __device__ __forceinline__ void gemv_preload(const GemvArgs& a, int gw, int nw, 
 //   gemv_stage_commit: writes them to LDS (x * gain when NORM), handles what exceeds R * THREADS
 //                      float4s in further rounds, and leaves each wave's partial sum of squares in red.
 // After the workgroup barrier that must follow, gemv_inv_rms gives 1/sqrt(mean(x^2) + eps) per column;
-// it is applied to the finished dot products.  COHERENT: the input was written by other workgroups of
-// the same launch and is read with agent-scope loads.
+// it is applied to the finished dot products.
 template <int NC, int R>
 struct GemvStageRegs {
     float4 v[NC][R];
     float4 g[R];
 };
 
-template <bool COHERENT>
-__device__ __forceinline__ float4 gemv_load_f4(const float* src) {
-    if (COHERENT) {
-        const unsigned long long lo = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long hi = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return make_float4(__uint_as_float((unsigned)lo), __uint_as_float((unsigned)(lo >> 32)),
-                           __uint_as_float((unsigned)hi), __uint_as_float((unsigned)(hi >> 32)));
-    }
-    return *reinterpret_cast<const float4*>(src);
-}
-
-template <int NC, bool NORM, bool COHERENT, int THREADS, int R>
+template <int NC, bool NORM, int THREADS, int R>
 __device__ __forceinline__ void gemv_stage_issue(const GemvArgs& a, int tid, GemvStageRegs<NC, R>& regs) {
     const int f4_used = a.K / 4;
 #pragma unroll
@@ -156,12 +143,12 @@ __device__ __forceinline__ void gemv_stage_issue(const GemvArgs& a, int tid, Gem
 #pragma unroll
         for (int n = 0; n < NC; ++n) {
             regs.v[n][r] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n < a.ncols && i4 < f4_used) regs.v[n][r] = gemv_load_f4<COHERENT>(a.x + (size_t)n * a.x_stride + i4 * 4);
+            if (n < a.ncols && i4 < f4_used) regs.v[n][r] = *reinterpret_cast<const float4*>(a.x + (size_t)n * a.x_stride + i4 * 4);
         }
     }
 }
 
-template <typename W, int NC, bool NORM, bool COHERENT, int THREADS, int R>
+template <typename W, int NC, bool NORM, int THREADS, int R>
 __device__ __forceinline__ void gemv_stage_commit(const GemvArgs& a, int tid, float4* xs, GemvStageRegs<NC, R>& regs,
                                                   float (*red)[THREADS / 64]) {
     const int K = a.K;
@@ -191,7 +178,7 @@ __device__ __forceinline__ void gemv_stage_commit(const GemvArgs& a, int tid, fl
 #pragma unroll
         for (int n = 0; n < NC; ++n) {
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (n < a.ncols && i4 < f4_used) t = gemv_load_f4<COHERENT>(a.x + (size_t)n * a.x_stride + i4 * 4);
+            if (n < a.ncols && i4 < f4_used) t = *reinterpret_cast<const float4*>(a.x + (size_t)n * a.x_stride + i4 * 4);
             put(i4, n, t, g);
         }
     }
@@ -270,12 +257,11 @@ struct GemvEpBuf {
     int row[kGemvEpCap];
 };
 
-// Write-out of one finished unit for column n.  COHERENT: outputs that other workgroups of the same
-// launch will read are written (and the residual read) with agent-scope accesses.
-template <int MODE, bool COHERENT>
+// Write-out of one finished unit for column n.
+template <int MODE>
 __device__ __forceinline__ void gemv_epilogue(const GemvArgs& a, int n, int row, float s0, float s1) {
     float* o = a.out + (size_t)n * a.out_stride + row;
-    auto put = [](float* p, float v) { if (COHERENT) st_agent(p, v); else *p = v; };
+    auto put = [](float* p, float v) { *p = v; };
     if (MODE == MODE_STORE) { put(o, s0); put(o + 1, s1); }
     else if (MODE == MODE_RESID) { }                   // handled in gemv_run with the prefetched residual
     else if (MODE == MODE_SWIGLU) { put(o, s0 / (1.0f + expf(-s0)) * s1); }
@@ -284,14 +270,7 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs& a, int n, int row,
         const int half = a.hd >> 1, head = row / a.hd, j = row % a.hd;
         const int c = a.col0 + n;
         if (head < a.H + a.H_kv) {
-            float2 cs;
-            if (COHERENT) {
-                const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(&a.rope_cs[(size_t)c * half + j]),
-                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                cs.x = __uint_as_float((unsigned)bits); cs.y = __uint_as_float((unsigned)(bits >> 32));
-            } else {
-                cs = a.rope_cs[(size_t)c * half + j];
-            }
+            const float2 cs = a.rope_cs[(size_t)c * half + j];
             const float y0 = s0 * cs.x - s1 * cs.y, y1 = s0 * cs.y + s1 * cs.x;
             s0 = y0; s1 = y1;
         }
@@ -303,22 +282,22 @@ __device__ __forceinline__ void gemv_epilogue(const GemvArgs& a, int n, int row,
             kv_store(base, idx, a.kv_dtype, s0);
             kv_store(base, idx + half, a.kv_dtype, s1);
         }
-        if (head < a.H || COHERENT) { put(o, s0); put(o + half, s1); }   // q; a fused step also keeps the new k, v rows here
+        if (head < a.H) { put(o, s0); put(o + half, s1); }   // q
     }
 }
 
-template <int NC, int MODE, bool COHERENT>
+template <int NC, int MODE>
 __device__ __forceinline__ void gemv_flush(const GemvArgs& a, const GemvEpBuf<NC>& ep, int n_ep) {
     const int lane = threadIdx.x & 63;
     for (int e = lane; e < n_ep; e += 64) {
 #pragma unroll
         for (int n = 0; n < NC; ++n)
-            if (n < a.ncols) gemv_epilogue<MODE, COHERENT>(a, n, ep.row[e], ep.s[e][n][0], ep.s[e][n][1]);
+            if (n < a.ncols) gemv_epilogue<MODE>(a, n, ep.row[e], ep.s[e][n][0], ep.s[e][n][1]);
     }
 }
 
 // Main loop of a phase: consume the wave's steps, keeping the ring full.  `ep` is this wave's buffer.
-template <typename W, int NC, int MODE, int D, bool COHERENT>
+template <typename W, int NC, int MODE, int D>
 __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, int gw, int nw, GemvPipe<W, D>& p, GemvEpBuf<NC>& ep,
                                          const float (&scale)[NC]) {
     const int lane = threadIdx.x & 63;
@@ -337,13 +316,8 @@ __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, in
             res0[n] = 0.f; res1[n] = 0.f;
             if (e_unit < n_units && n < a.ncols) {
                 const float* o = a.out + (size_t)n * a.out_stride + 2 * e_unit;
-                if (COHERENT) {
-                    const unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(o), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    res0[n] = __uint_as_float((unsigned)bits); res1[n] = __uint_as_float((unsigned)(bits >> 32));
-                } else {
-                    const float2 v = *reinterpret_cast<const float2*>(o);
-                    res0[n] = v.x; res1[n] = v.y;
-                }
+                const float2 v = *reinterpret_cast<const float2*>(o);
+                res0[n] = v.x; res1[n] = v.y;
             }
         }
     }
@@ -397,12 +371,12 @@ __device__ __forceinline__ void gemv_run(const GemvArgs& a, const float4* xs, in
                 if (n < a.ncols) {
                     float* o = a.out + (size_t)n * a.out_stride + ep.row[lane];
                     const float y0 = res0[n] + ep.s[lane][n][0], y1 = res1[n] + ep.s[lane][n][1];
-                    if (COHERENT) { st_agent(o, y0); st_agent(o + 1, y1); } else { o[0] = y0; o[1] = y1; }
+                    o[0] = y0; o[1] = y1;
                 }
             }
         }
     } else {
-        gemv_flush<NC, MODE, COHERENT>(a, ep, n_ep);
+        gemv_flush<NC, MODE>(a, ep, n_ep);
     }
 }
 

@@ -33,13 +33,13 @@ __global__ __launch_bounds__(kGemvThreads) void gemv_alu_kernel(GemvArgs a) {
     const int gw = wave * gridDim.x + blockIdx.x, nw = gridDim.x * kGemvWaves;
     GemvStageRegs<NC, R> regs;
     GemvPipe<W, kGemvDepth> pipe;
-    gemv_stage_issue<NC, NORM, false, kGemvThreads, R>(a, tid, regs);          // activations first ...
+    gemv_stage_issue<NC, NORM, kGemvThreads, R>(a, tid, regs);          // activations first ...
     gemv_preload<W, MODE, kGemvDepth>(a, gw, nw, pipe);                          // ... the weight stream right behind them
-    gemv_stage_commit<W, NC, NORM, false, kGemvThreads, R>(a, tid, xs, regs, red);
+    gemv_stage_commit<W, NC, NORM, kGemvThreads, R>(a, tid, xs, regs, red);
     __syncthreads();
     float rinv[NC];
     gemv_inv_rms<NC, NORM, kGemvWaves>(a, red, rinv);
-    gemv_run<W, NC, MODE, kGemvDepth, false>(a, xs, gw, nw, pipe, ep[wave], rinv);
+    gemv_run<W, NC, MODE, kGemvDepth>(a, xs, gw, nw, pipe, ep[wave], rinv);
 }
 
 template <typename W, int NC>

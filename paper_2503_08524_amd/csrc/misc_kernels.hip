@@ -181,6 +181,28 @@ __global__ __launch_bounds__(64) void fill_kernel(FillArgs a, int bytes_per_vec)
     }
 }
 
+// ---------------- read-only streaming yardstick ----------------
+// What the memory system gives a pure read stream issued the way the projections issue theirs (16 bytes per lane,
+// streaming loads, eight in flight per lane, one contiguous band at a time): every workgroup XORs its share and
+// one lane per wave stores the result so that the loads cannot be dropped.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 7 * stride < n16; i += 8 * stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] = load_stream16(src + i + r * stride);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) acc ^= v[r];
+    }
+    for (; i < n16; i += stride) acc ^= load_stream16(src + i);
+    unsigned x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x ^= __shfl_xor(x, o, 64);
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = x;
+}
+
 // ---------------- state words of a decode step that runs in the static scratch array ----------------
 __global__ __launch_bounds__(256) void static_seed_kernel(StaticSeed seed, double* __restrict__ inv_freq, int half_hd, int* __restrict__ row0,
                                                           int* __restrict__ tickets, int n_tickets, int* __restrict__ gemm_tickets,
@@ -198,6 +220,11 @@ int launch_static_seed(const StaticSeed& seed, double* inv_freq, int half_hd, in
                        int* gemm_tickets, int n_gemm_tickets, hipStream_t s) {
     hipLaunchKernelGGL(static_seed_kernel, dim3(8), dim3(256), 0, s, seed, inv_freq, half_hd, row0, tickets, n_tickets, gemm_tickets,
                        n_gemm_tickets);
+    return (int)hipGetLastError();
+}
+
+int launch_stream_read(const void* src, size_t bytes, unsigned* sink, int n_wg, hipStream_t s) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(256), 0, s, static_cast<const u32x4*>(src), bytes / 16, sink);
     return (int)hipGetLastError();
 }
 

@@ -418,21 +418,100 @@ __device__ __forceinline__ attn_half8 attn_v_fragment(const char* vbuf, int nt, 
     return __builtin_bit_cast(attn_half8, both);
 }
 
-template <int NW, int G>
+// PL planes per staged tile: 1 for an fp16 cache (the rows as they are), 2 for an fp32 cache (each row split into
+// fp16 hi + lo, so that both contractions keep the cache's precision: K.q = Khi.q + Klo.q, P.V = P.Vhi + P.Vlo).
+template <int NW, int G, int PL = 1>
 struct AttnMfmaShared {
     union {
         struct {
-            char k[NW][16 * kAttnPitch];   // one K tile per wave
-            char v[NW][32 * kAttnPitch];   // one 32-row V tile per wave
-            float keep[NW][16];            // rescale factor of each head, from the score layout to the output layout
+            char k[NW][PL][16 * kAttnPitch];   // one K tile per wave
+            char v[NW][PL][32 * kAttnPitch];   // one 32-row V tile per wave
+            float keep[NW][16];                // rescale factor of each head, from the score layout to the output layout
         } stage;
         AttnShared<128, NW, G> merge;
     };
 };
 
-template <bool ROPE, int NW, int G>
-__device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, int h0, int c, AttnMfmaShared<NW, G>& sh) {
+// Cache rows -> staged fp16 tiles.  A wave loads 32 rows of 128 elements with coalesced 16-byte loads and writes them
+// into LDS tiles of kAttnPitch bytes per row: fp16 rows as they are (8 loads of K and of V per lane; lane = (row % 4, 16-byte
+// segment)), fp32 rows split hi + lo on the way (16 loads each; lane = (row % 2, segment of 4 floats)).
+template <typename T> struct AttnStage;
+template <> struct AttnStage<f16_t> {
+    static constexpr int PL = 1, NLOAD = 8;
+    template <bool STREAM>
+    static __device__ __forceinline__ void load(const f16_t* base, int r0, int j1, int lane, u32x4 (&reg)[NLOAD]) {
+        const int lrow = lane >> 4, lseg = lane & 15;
+#pragma unroll
+        for (int q = 0; q < NLOAD; ++q) {
+            int row = r0 + 4 * q + lrow;
+            row = row < j1 ? row : j1 - 1;
+            const f16_t* p = base + (size_t)row * 128 + 8 * lseg;
+            reg[q] = STREAM ? load_stream16(p) : *reinterpret_cast<const u32x4*>(p);
+        }
+    }
+    // rows [16 t, 16 t + 16) of the 32 loaded rows -> tile rows 0..15 (n_tiles = 1), or all 32 rows (n_tiles = 2, t = 0)
+    static __device__ __forceinline__ void put(char (*buf)[16 * kAttnPitch], const u32x4 (&reg)[NLOAD], int t, int lane) {
+        const int lrow = lane >> 4, lseg = lane & 15;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *reinterpret_cast<u32x4*>(buf[0] + (4 * q + lrow) * kAttnPitch + lseg * 16) = reg[4 * t + q];
+    }
+    static __device__ __forceinline__ void put32(char (*buf)[32 * kAttnPitch], const u32x4 (&reg)[NLOAD], int lane) {
+        const int lrow = lane >> 4, lseg = lane & 15;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) *reinterpret_cast<u32x4*>(buf[0] + (4 * q + lrow) * kAttnPitch + lseg * 16) = reg[q];
+    }
+};
+template <> struct AttnStage<float> {
+    static constexpr int PL = 2, NLOAD = 16;
+    template <bool STREAM>
+    static __device__ __forceinline__ void load(const float* base, int r0, int j1, int lane, u32x4 (&reg)[NLOAD]) {
+        const int lrow = lane >> 5, lseg = lane & 31;
+#pragma unroll
+        for (int q = 0; q < NLOAD; ++q) {
+            int row = r0 + 2 * q + lrow;
+            row = row < j1 ? row : j1 - 1;
+            const float* p = base + (size_t)row * 128 + 4 * lseg;
+            reg[q] = STREAM ? load_stream16(p) : *reinterpret_cast<const u32x4*>(p);
+        }
+    }
+    static __device__ __forceinline__ void split(const u32x4& v, uint2& hi, uint2& lo) {
+        typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+        half4 h, l;
+        const float f[4] = {__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w)};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h[e] = (f16_t)fminf(fmaxf(f[e], -65504.f), 65504.f);
+            l[e] = (f16_t)(f[e] - (float)h[e]);
+        }
+        hi = __builtin_bit_cast(uint2, h);
+        lo = __builtin_bit_cast(uint2, l);
+    }
+    static __device__ __forceinline__ void put(char (*buf)[16 * kAttnPitch], const u32x4 (&reg)[NLOAD], int t, int lane) {
+        const int lrow = lane >> 5, lseg = lane & 31;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            uint2 hi, lo;
+            split(reg[8 * t + q], hi, lo);
+            *reinterpret_cast<uint2*>(buf[0] + (2 * q + lrow) * kAttnPitch + lseg * 8) = hi;
+            *reinterpret_cast<uint2*>(buf[1] + (2 * q + lrow) * kAttnPitch + lseg * 8) = lo;
+        }
+    }
+    static __device__ __forceinline__ void put32(char (*buf)[32 * kAttnPitch], const u32x4 (&reg)[NLOAD], int lane) {
+        const int lrow = lane >> 5, lseg = lane & 31;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            uint2 hi, lo;
+            split(reg[q], hi, lo);
+            *reinterpret_cast<uint2*>(buf[0] + (2 * q + lrow) * kAttnPitch + lseg * 8) = hi;
+            *reinterpret_cast<uint2*>(buf[1] + (2 * q + lrow) * kAttnPitch + lseg * 8) = lo;
+        }
+    }
+};
+
+template <typename T, bool ROPE, int NW, int G>
+__device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, int h0, int c, AttnMfmaShared<NW, G, AttnStage<T>::PL>& sh) {
     constexpr int HD = 128;
+    constexpr int PL = AttnStage<T>::PL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int seq = a.cm.seq(c);
@@ -445,8 +524,8 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
     const int n_live = (ctx + a.split_len - 1) / a.split_len;
     const int kvh = h0 / (a.H / a.H_kv);
     const size_t head_off = (((size_t)seq * a.H_kv + kvh) * a.max_seq + row0) * HD;
-    const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
-    const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
+    const T* Kb = static_cast<const T*>(a.k_cache) + head_off;
+    const T* Vb = static_cast<const T*>(a.v_cache) + head_off;
     const float scale = 1.4426950408889634f / sqrtf((float)HD);      // scores in log2 units
 
     // ---- q as the B operand: lane (i, g) holds q[h0 + i][32 kk + 8 g .. + 8], kk = 0..3, scaled, hi + lo ----
@@ -490,7 +569,7 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
     }
 
     // ---- the newest row in the layout of the staged tiles: lane (.., seg = lane % 16) holds dims 8 seg .. + 8 ----
-    attn_half8 nk, nv;
+    attn_half8 nk[PL], nv[PL];
     if (has_new) {
         const int seg = lane & 15;
         const bool upper = seg >= 8;
@@ -505,12 +584,25 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
             const float y0 = upper ? par.x * t.y + own.x * t.x : own.x * t.x - par.x * t.y;
             const float y1 = upper ? par.y * t.w + own.y * t.z : own.y * t.z - par.y * t.w;
             const float2 vv = *reinterpret_cast<const float2*>(vp + e);
-            nk[e] = (f16_t)fminf(fmaxf(y0, -65504.f), 65504.f);     nk[e + 1] = (f16_t)fminf(fmaxf(y1, -65504.f), 65504.f);
-            nv[e] = (f16_t)fminf(fmaxf(vv.x, -65504.f), 65504.f);   nv[e + 1] = (f16_t)fminf(fmaxf(vv.y, -65504.f), 65504.f);
+            const float val[4] = {y0, y1, vv.x, vv.y};
+            f16_t h[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) h[u] = (f16_t)fminf(fmaxf(val[u], -65504.f), 65504.f);
+            nk[0][e] = h[0]; nk[0][e + 1] = h[1]; nv[0][e] = h[2]; nv[0][e + 1] = h[3];
+            if (PL == 2) {                             // an fp32 cache keeps the row as it is: staged as hi + lo
+                nk[PL - 1][e] = (f16_t)(y0 - (float)h[0]);   nk[PL - 1][e + 1] = (f16_t)(y1 - (float)h[1]);
+                nv[PL - 1][e] = (f16_t)(vv.x - (float)h[2]); nv[PL - 1][e + 1] = (f16_t)(vv.y - (float)h[3]);
+                if (wave == 0 && lane < 16) {
+                    float* kd = reinterpret_cast<float*>(const_cast<T*>(Kb)) + (size_t)(ctx - 1) * HD + 8 * seg + e;
+                    float* vd = reinterpret_cast<float*>(const_cast<T*>(Vb)) + (size_t)(ctx - 1) * HD + 8 * seg + e;
+                    *reinterpret_cast<float2*>(kd) = make_float2(y0, y1);
+                    *reinterpret_cast<float2*>(vd) = vv;
+                }
+            }
         }
-        if (wave == 0 && lane < 16) {                  // one copy of the row goes to the cache (the caches are this launch's to extend)
-            *reinterpret_cast<attn_half8*>(const_cast<f16_t*>(Kb) + (size_t)(ctx - 1) * HD + 8 * seg) = nk;
-            *reinterpret_cast<attn_half8*>(const_cast<f16_t*>(Vb) + (size_t)(ctx - 1) * HD + 8 * seg) = nv;
+        if (PL == 1 && wave == 0 && lane < 16) {       // one copy of the row goes to the cache (the caches are this launch's to extend)
+            *reinterpret_cast<attn_half8*>(reinterpret_cast<f16_t*>(const_cast<T*>(Kb)) + (size_t)(ctx - 1) * HD + 8 * seg) = nk[0];
+            *reinterpret_cast<attn_half8*>(reinterpret_cast<f16_t*>(const_cast<T*>(Vb)) + (size_t)(ctx - 1) * HD + 8 * seg) = nv[0];
         }
     }
 
@@ -519,36 +611,36 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
     attn_f32x4 acc[8];                                 // [column tile nt]: lane (i, g) holds column 16 nt + i, heads 4g..4g+3
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) acc[nt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
-    char* kbuf = sh.stage.k[wave];
-    char* vbuf = sh.stage.v[wave];
+    char (*kbuf)[16 * kAttnPitch] = sh.stage.k[wave];
+    char (*vbuf)[32 * kAttnPitch] = sh.stage.v[wave];
     float* keepbuf = sh.stage.keep[wave];
-    const int lrow = lane >> 4, lseg = lane & 15;      // coalesced loads: 16 lanes read 256 contiguous bytes of one row
+    const int lseg = lane & 15;
 
     for (int r0 = j0 + wave * 32; r0 < j1; r0 += NW * 32) {
-        uint4 kreg[2][4], vreg[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int row = r0 + 4 * q + lrow;
-            row = row < j1 ? row : j1 - 1;
-            kreg[q >> 2][q & 3] = __builtin_bit_cast(uint4, load_stream16(Kb + (size_t)row * HD + 8 * lseg));
-            vreg[q] = __builtin_bit_cast(uint4, load_stream16(Vb + (size_t)row * HD + 8 * lseg));
-        }
+        u32x4 kreg[AttnStage<T>::NLOAD], vreg[AttnStage<T>::NLOAD];
+        AttnStage<T>::template load<true>(Kb, r0, j1, lane, kreg);      // each row is read once per step: streaming loads
+        AttnStage<T>::template load<true>(Vb, r0, j1, lane, vreg);
         // ---- scores^T of the two K tiles ----
         attn_f32x4 S[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
+            AttnStage<T>::put(kbuf, kreg, t, lane);
+            if (has_new && ctx - 1 >= r0 + 16 * t && ctx - 1 < r0 + 16 * t + 16 && lane < 16) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<uint4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[t][q];
-            if (has_new && ctx - 1 >= r0 + 16 * t && ctx - 1 < r0 + 16 * t + 16 && lane < 16)
-                *reinterpret_cast<attn_half8*>(kbuf + (ctx - 1 - r0 - 16 * t) * kAttnPitch + lseg * 16) = nk;
+                for (int pl = 0; pl < PL; ++pl)
+                    *reinterpret_cast<attn_half8*>(kbuf[pl] + (ctx - 1 - r0 - 16 * t) * kAttnPitch + lseg * 16) = nk[pl];
+            }
             __builtin_amdgcn_wave_barrier();
             S[t] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf + i * kAttnPitch + kk * 64 + g * 16);
+                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf[0] + i * kAttnPitch + kk * 64 + g * 16);
                 S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qhi[kk], S[t], 0, 0, 0);
                 S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qlo[kk], S[t], 0, 0, 0);
+                if (PL == 2) {
+                    const attn_half8 al = *reinterpret_cast<const attn_half8*>(kbuf[PL - 1] + i * kAttnPitch + kk * 64 + g * 16);
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, qhi[kk], S[t], 0, 0, 0);
+                }
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -582,19 +674,24 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
         // ---- the heads' rescale factors, from lane = head to lane (column, heads 4g..4g+3) ----
         if (g == 0) keepbuf[i] = keep;
         // ---- V tile ----
+        AttnStage<T>::put32(vbuf, vreg, lane);
+        if (has_new && ctx - 1 >= r0 && ctx - 1 < r0 + 32 && lane < 16) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<uint4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
-        if (has_new && ctx - 1 >= r0 && ctx - 1 < r0 + 32 && lane < 16)
-            *reinterpret_cast<attn_half8*>(vbuf + (ctx - 1 - r0) * kAttnPitch + lseg * 16) = nv;
+            for (int pl = 0; pl < PL; ++pl)
+                *reinterpret_cast<attn_half8*>(vbuf[pl] + (ctx - 1 - r0) * kAttnPitch + lseg * 16) = nv[pl];
+        }
         __builtin_amdgcn_wave_barrier();
         const float4 kf = *reinterpret_cast<const float4*>(keepbuf + 4 * g);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
-            const attn_half8 vb = attn_v_fragment(vbuf, nt, lane);
+            const attn_half8 vb = attn_v_fragment(vbuf[0], nt, lane);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
+            if (PL == 2) {
+                const attn_half8 vl = attn_v_fragment(vbuf[PL - 1], nt, lane);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vl, acc[nt], 0, 0, 0);
+            }
         }
         __builtin_amdgcn_wave_barrier();               // the tiles are free for the next 32 rows
     }
@@ -619,9 +716,10 @@ __device__ __forceinline__ void attn_split_mfma(const AttnArgs& a, int split, in
 // queries (columns c0 .. c0 + QT - 1) times the GH query heads of one KV head, so a cache row is read once per QT
 // queries.  Entry e = query e / GH, head h0 + e % GH; its context ends at its own position (causal mask per
 // entry).  The K/V rows of the chunk are already in the cache (rope_append_kernel ran before), q is rotated.
-template <int NW, int GH>
-__device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, int h0, int c0, AttnMfmaShared<NW, 16>& sh) {
+template <typename T, int NW, int GH>
+__device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, int h0, int c0, AttnMfmaShared<NW, 16, AttnStage<T>::PL>& sh) {
     constexpr int HD = 128;
+    constexpr int PL = AttnStage<T>::PL;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int c_last = min(c0 + 16 / GH, a.ncols) - 1;               // last column of the tile that exists
@@ -634,8 +732,8 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
     const int n_live = (ctx_max + a.split_len - 1) / a.split_len;
     const int kvh = h0 / (a.H / a.H_kv);
     const size_t head_off = (((size_t)seq * a.H_kv + kvh) * a.max_seq + row0) * HD;
-    const f16_t* Kb = static_cast<const f16_t*>(a.k_cache) + head_off;
-    const f16_t* Vb = static_cast<const f16_t*>(a.v_cache) + head_off;
+    const T* Kb = static_cast<const T*>(a.k_cache) + head_off;
+    const T* Vb = static_cast<const T*>(a.v_cache) + head_off;
     const float scale = 1.4426950408889634f / sqrtf((float)HD);
     const int ci = c0 + i / GH;                                      // this lane's entry: column, head, end of context
     const bool live = ci < a.ncols;
@@ -662,33 +760,29 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
     attn_f32x4 acc[8];
 #pragma unroll
     for (int nt = 0; nt < 8; ++nt) acc[nt] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
-    char* kbuf = sh.stage.k[wave];
-    char* vbuf = sh.stage.v[wave];
+    char (*kbuf)[16 * kAttnPitch] = sh.stage.k[wave];
+    char (*vbuf)[32 * kAttnPitch] = sh.stage.v[wave];
     float* keepbuf = sh.stage.keep[wave];
-    const int lrow = lane >> 4, lseg = lane & 15;
 
     for (int r0 = j0 + wave * 32; r0 < j1; r0 += NW * 32) {
-        u32x4 kreg[8], vreg[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            int row = r0 + 4 * q + lrow;
-            row = row < j1 ? row : j1 - 1;
-            kreg[q] = *reinterpret_cast<const u32x4*>(Kb + (size_t)row * HD + 8 * lseg);   // re-read by the next tiles: cached
-            vreg[q] = *reinterpret_cast<const u32x4*>(Vb + (size_t)row * HD + 8 * lseg);
-        }
+        u32x4 kreg[AttnStage<T>::NLOAD], vreg[AttnStage<T>::NLOAD];
+        AttnStage<T>::template load<false>(Kb, r0, j1, lane, kreg);     // re-read by the next tiles: cached
+        AttnStage<T>::template load<false>(Vb, r0, j1, lane, vreg);
         attn_f32x4 S[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<u32x4*>(kbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = kreg[4 * t + q];
+            AttnStage<T>::put(kbuf, kreg, t, lane);
             __builtin_amdgcn_wave_barrier();
             S[t] = attn_f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf + i * kAttnPitch + kk * 64 + g * 16);
+                const attn_half8 af = *reinterpret_cast<const attn_half8*>(kbuf[0] + i * kAttnPitch + kk * 64 + g * 16);
                 S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qhi[kk], S[t], 0, 0, 0);
                 S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(af, qlo[kk], S[t], 0, 0, 0);
+                if (PL == 2) {
+                    const attn_half8 al = *reinterpret_cast<const attn_half8*>(kbuf[PL - 1] + i * kAttnPitch + kk * 64 + g * 16);
+                    S[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, qhi[kk], S[t], 0, 0, 0);
+                }
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -721,17 +815,19 @@ __device__ __forceinline__ void attn_qtile_mfma(const AttnArgs& a, int split, in
         lsum = lsum * keep + ps;
         m = m_new;
         if (g == 0) keepbuf[i] = keep;
-#pragma unroll
-        for (int q = 0; q < 8; ++q)
-            *reinterpret_cast<u32x4*>(vbuf + (4 * q + lrow) * kAttnPitch + lseg * 16) = vreg[q];
+        AttnStage<T>::put32(vbuf, vreg, lane);
         __builtin_amdgcn_wave_barrier();
         const float4 kf = *reinterpret_cast<const float4*>(keepbuf + 4 * g);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt) {
             acc[nt][0] *= kf.x; acc[nt][1] *= kf.y; acc[nt][2] *= kf.z; acc[nt][3] *= kf.w;
-            const attn_half8 vb = attn_v_fragment(vbuf, nt, lane);
+            const attn_half8 vb = attn_v_fragment(vbuf[0], nt, lane);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vb, acc[nt], 0, 0, 0);
             acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(plo, vb, acc[nt], 0, 0, 0);
+            if (PL == 2) {
+                const attn_half8 vl = attn_v_fragment(vbuf[PL - 1], nt, lane);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(phi, vl, acc[nt], 0, 0, 0);
+            }
         }
         __builtin_amdgcn_wave_barrier();
     }

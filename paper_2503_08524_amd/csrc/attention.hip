@@ -22,39 +22,65 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     attn_split<T, HD, false, 4, G, ROPE>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
 }
 
-template <int G, bool ROPE>
+// The staging tiles of an fp32 cache (hi + lo planes, 105 KB for four waves) exceed what a kernel may declare statically:
+// that variant takes its LDS as dynamic shared memory.
+extern __shared__ __align__(16) char attn_dyn_lds[];
+
+template <typename T, int G, bool ROPE>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a) {
-    __shared__ AttnMfmaShared<4, G> sh;
-    attn_split_mfma<ROPE, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
+    typedef AttnMfmaShared<4, G, AttnStage<T>::PL> Shared;
+    if constexpr (AttnStage<T>::PL == 1) {
+        __shared__ Shared sh;
+        attn_split_mfma<T, ROPE, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, sh);
+    } else {
+        attn_split_mfma<T, ROPE, 4, G>(a, blockIdx.x, blockIdx.y * G, blockIdx.z, *reinterpret_cast<Shared*>(attn_dyn_lds));
+    }
 }
 
 // grid: (split, KV-head group, tile of 16 / GH consecutive queries)
-template <int GH>
+template <typename T, int GH>
 __global__ __launch_bounds__(256) void attn_qtile_kernel(AttnArgs a) {
-    __shared__ AttnMfmaShared<4, 16> sh;
-    attn_qtile_mfma<4, GH>(a, blockIdx.x, blockIdx.y * GH, blockIdx.z * (16 / GH), sh);
+    typedef AttnMfmaShared<4, 16, AttnStage<T>::PL> Shared;
+    if constexpr (AttnStage<T>::PL == 1) {
+        __shared__ Shared sh;
+        attn_qtile_mfma<T, 4, GH>(a, blockIdx.x, blockIdx.y * GH, blockIdx.z * (16 / GH), sh);
+    } else {
+        attn_qtile_mfma<T, 4, GH>(a, blockIdx.x, blockIdx.y * GH, blockIdx.z * (16 / GH), *reinterpret_cast<Shared*>(attn_dyn_lds));
+    }
+}
+
+// launch with the LDS the element type needs (dynamic for the two-plane variant, whose size must be allowed once per kernel)
+template <typename T, typename Shared, typename K>
+int launch_mfma(K kernel, dim3 grid, const AttnArgs& a, hipStream_t s) {
+    size_t dyn = 0;
+    if constexpr (AttnStage<T>::PL == 2) {
+        dyn = sizeof(Shared);
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(Shared));
+        if (once != hipSuccess) return (int)once;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(256), dyn, s, a);
+    return (int)hipGetLastError();
 }
 
 template <typename T, int HD, bool ROPE>
 int launch_g(const AttnArgs& a, bool use_mfma, hipStream_t s) {
     const int group = a.H / a.H_kv;
-    if constexpr (std::is_same<T, f16_t>::value && HD == 128 && !ROPE) {
+    if constexpr (HD == 128 && !ROPE) {
         if (a.qtile && (group == 1 || group == 2 || group == 4 || group == 8) && use_mfma) {
             const int qt = 16 / group;
             dim3 grid(a.n_splits, a.H / group, (a.ncols + qt - 1) / qt);
-            if (group == 8) hipLaunchKernelGGL((attn_qtile_kernel<8>), grid, dim3(256), 0, s, a);
-            else if (group == 4) hipLaunchKernelGGL((attn_qtile_kernel<4>), grid, dim3(256), 0, s, a);
-            else if (group == 2) hipLaunchKernelGGL((attn_qtile_kernel<2>), grid, dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((attn_qtile_kernel<1>), grid, dim3(256), 0, s, a);
-            return (int)hipGetLastError();
+            typedef AttnMfmaShared<4, 16, AttnStage<T>::PL> Shared;
+            if (group == 8) return launch_mfma<T, Shared>(attn_qtile_kernel<T, 8>, grid, a, s);
+            if (group == 4) return launch_mfma<T, Shared>(attn_qtile_kernel<T, 4>, grid, a, s);
+            if (group == 2) return launch_mfma<T, Shared>(attn_qtile_kernel<T, 2>, grid, a, s);
+            return launch_mfma<T, Shared>(attn_qtile_kernel<T, 1>, grid, a, s);
         }
     }
-    if constexpr (std::is_same<T, f16_t>::value && HD == 128) {
+    if constexpr (HD == 128) {
         if ((group == 4 || group == 8) && use_mfma) {
             dim3 grid(a.n_splits, a.H / group, a.ncols);
-            if (group == 8) hipLaunchKernelGGL((attn_mfma_kernel<8, ROPE>), grid, dim3(256), 0, s, a);
-            else hipLaunchKernelGGL((attn_mfma_kernel<4, ROPE>), grid, dim3(256), 0, s, a);
-            return (int)hipGetLastError();
+            if (group == 8) return launch_mfma<T, AttnMfmaShared<4, 8, AttnStage<T>::PL>>(attn_mfma_kernel<T, 8, ROPE>, grid, a, s);
+            return launch_mfma<T, AttnMfmaShared<4, 4, AttnStage<T>::PL>>(attn_mfma_kernel<T, 4, ROPE>, grid, a, s);
         }
     }
     const int g = (group == 2 || group == 4 || group == 8) ? group : 1;    // other group sizes: one query head per workgroup

@@ -224,7 +224,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->tn = tuning_from_env();
     // grouped-query models on the MFMA attention kernel (fp16 cache, head_dim 128, 4 or 8 heads per KV head) do better with
     // one workgroup per CU (70B shape, batch 8: 24.41 against 24.55 ms a step), the others with two (13B, batch 4: 5.71 against 5.78)
-    c->attn_wgs_per_cu = (desc->kv_dtype == D3_F16 && desc->head_dim == 128 && desc->n_kv_heads > 0 &&
+    c->attn_wgs_per_cu = (desc->head_dim == 128 && desc->n_kv_heads > 0 &&
                           (desc->n_heads / desc->n_kv_heads == 4 || desc->n_heads / desc->n_kv_heads == 8)) ? 1 : 2;
     c->prefill_by_seq = env_int("D3_PREFILL_BY_SEQ", 0, 1, 1) != 0;
     c->attn_wgs_per_cu = env_int("D3_ATTN_WGS_PER_CU", 1, 16, c->attn_wgs_per_cu);
@@ -394,7 +394,7 @@ int forward(d3_ctx* c, const int32_t* tokens, ColMap cm, int ncols, const int32_
 
     // a prompt chunk of one sequence (consecutive positions): tiles of queries share the cache rows they read
     const int grp = d.n_heads / d.n_kv_heads;
-    const bool qtile = c->prefill_by_seq && mfma && cm.B == 1 && ncols >= 2 && d.kv_dtype == D3_F16 && hd == 128 &&
+    const bool qtile = c->prefill_by_seq && mfma && cm.B == 1 && ncols >= 2 && hd == 128 &&
                        (grp == 1 || grp == 2 || grp == 4 || grp == 8);
     int split_len, n_splits;
     pick_splits(c, ncols, cm.pos(ncols - 1) + 1, c->attn_wgs_per_cu * c->n_cu, &split_len, &n_splits, qtile);

@@ -133,6 +133,16 @@ def test_small_gqa(B, kv):
     _run(SMALL_GQA, B, 37, 6, 0.8, 1, forced_seed=8, kv_dtype=kv)
 
 
+@pytest.mark.parametrize("B,P", [(2, 300), (1, 700)])
+def test_fp32_cache_on_the_matrix_core_attention_kernels(B, P):
+    # grouped-query attention at head_dim 128 with an fp32 cache (what models deeper than 48 blocks get): the cache rows go
+    # to the matrix cores as fp16 hi + lo planes; prompt chunks of 128 + 128 + 44 columns (query tiles), decode contexts
+    # that span three and six splits, batch 1 (vector-ALU projections) and batch 2 (matrix-core projections).  The fp32
+    # rows leave nothing but arithmetic rounding: the logits must agree 100 times closer than the acceptance bound.
+    gpu, gens = _run(SMALL_GQA, B, P, 5, 0.8, 1, forced_seed=8, kv_dtype="f32")
+    helpers.compare(gpu, gens, 5, logit_atol=2e-4, hidden_tol=1e-4)
+
+
 @pytest.mark.parametrize("kv", ["f16", "f32"])
 def test_batch1_decode_grouped_query_head_dim_128(kv):
     _run(SMALL_GQA, 1, 70, 12, 0.85, 1, forced_seed=14, kv_dtype=kv)

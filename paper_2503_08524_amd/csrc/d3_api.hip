@@ -71,10 +71,11 @@ Layout make_layout(const d3_model_desc& d, size_t C, size_t CS, bool with_gemm_p
     l.qkv = take(C * qkv_dim * 4);
     l.attn_o = take(C * qdim * 4);
     l.act = take(C * (size_t)d.d_ffn * 4);
-    l.part_o = take(C * d.n_heads * kMaxSplits * (size_t)d.head_dim * 4);
-    l.part_ml = take(C * d.n_heads * kMaxSplits * 2 * 4);
+    const size_t PC = C < (size_t)kMaxCols ? C : (size_t)kMaxCols;   // a pass has at most kMaxCols * kMaxSplits (column, split) pairs
+    l.part_o = take(PC * d.n_heads * kMaxSplits * (size_t)d.head_dim * 4);
+    l.part_ml = take(PC * d.n_heads * kMaxSplits * 2 * 4);
     l.tickets = take(C * d.n_heads * 4);
-    l.logits = take(C * (size_t)d.vocab * 4);
+    l.logits = take(PC * (size_t)d.vocab * 4);                        // one row per sequence
     l.s_hi = take(CS * s_dim * 2);
     l.s_lo = take(CS * s_dim * 2);
     l.f_hi = take(CS * (size_t)d.d_ffn * 2);
@@ -84,15 +85,21 @@ Layout make_layout(const d3_model_desc& d, size_t C, size_t CS, bool with_gemm_p
     l.n_hi = take(CS * d.d_model * 2);
     l.n_lo = take(CS * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
-    l.h_skip = take(C * d.d_model * 4);
+    l.h_skip = take(PC * d.d_model * 4);                              // decode passes only
     l.gemm_part = take(with_gemm_part ? kGemmPartBytes : 0);
     l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
-    l.row0 = take(kPassCols * 4);
+    l.row0 = take(kMaxCols * 4);
     l.total = o;
     return l;
 }
-// The caller's workspace serves prompt chunks of up to kPassCols columns.
-Layout make_layout(const d3_model_desc& d) { return make_layout(d, kPassCols, kPassCols, true); }
+// Columns of a prompt chunk: a whole sequence if it fits kPassCols (one pass over the weights per sequence, and enough
+// column blocks for the 4096-row projections to fill the chip), never more than the cache can hold.
+int pass_cols(const d3_model_desc& d) {
+    const int need = (d.max_seq + 127) / 128 * 128;
+    return need < kPassCols ? need : kPassCols;
+}
+// The caller's workspace serves prompt chunks of up to pass_cols() columns.
+Layout make_layout(const d3_model_desc& d) { return make_layout(d, pass_cols(d), pass_cols(d), true); }
 
 }  // namespace
 
@@ -117,8 +124,8 @@ Tuning tuning_from_env() {
     t.wide_split_mb = (size_t)env_int("D3_WIDE_SPLIT_MB", 0, 1 << 20, 300);
     t.attn_mfma = env_int("D3_ATTN_MFMA", 0, 1, 1) != 0;
     t.attn_min_split = env_int("D3_ATTN_MIN_SPLIT", 64, 65536, 128) / 64 * 64;
-    const int pc = env_int("D3_PREFILL_COLS", 64, 128, 0);
-    t.prefill_cols = pc == 64 || pc == 128 ? pc : 0;
+    const int pc = env_int("D3_PREFILL_COLS", 64, kPassCols, 0);
+    t.prefill_cols = pc % 64 == 0 ? pc : 0;
     return t;
 }
 }  // namespace d3
@@ -232,7 +239,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     c->alu_ok = alu_fits(*desc);
     c->prof_class = D3_K_NONE; c->prof_used = 0;
     c->has_plan = false; c->n_steps = 0;
-    c->ragged = false; c->row0.assign(kPassCols, 0);
+    c->ragged = false; c->row0.assign(kMaxCols, 0);
     c->prefilled = false; c->B = 0; c->n_ctx = 0; c->last_step = 0;
     c->fill_mode = D3_FILL_COPY;
     c->skip_row = -1;
@@ -244,7 +251,7 @@ extern "C" int d3_create(d3_ctx** out, const d3_model_desc* desc, const d3_weigh
     inv.resize(desc->head_dim / 2);
     for (int j = 0; j < desc->head_dim / 2; ++j) inv[j] = std::pow((double)desc->rope_base, -2.0 * j / desc->head_dim);
     hipError_t e = hipMemcpy(c->at<double>(lay.inv_freq), inv.data(), inv.size() * sizeof(double), hipMemcpyHostToDevice);
-    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)kPassCols * desc->n_heads * sizeof(int));   // arrival counters start at 0
+    if (e == hipSuccess) e = hipMemset(c->at<int>(lay.tickets), 0, (size_t)pass_cols(*desc) * desc->n_heads * sizeof(int));   // arrival counters start at 0
     if (e == hipSuccess) e = hipMemset(c->at<int>(lay.gemm_tickets), 0, (size_t)kGemmPartTickets * sizeof(int));
     if (e != hipSuccess) { delete c; return fail(D3_EDEVICE, "d3_create: hipMemcpy/hipMemset failed: %s", hipGetErrorString(e)); }
     *out = c;
@@ -333,7 +340,10 @@ void pick_splits(const d3_ctx* c, int ncols, int ctx, int target_wgs, int* split
     int len = ((ctx + want - 1) / want + 63) / 64 * 64;
     if (len < min_len) len = min_len;
     int n = (ctx + len - 1) / len;
-    if (n > kMaxSplits) { len = ((ctx + kMaxSplits - 1) / kMaxSplits + 63) / 64 * 64; n = (ctx + len - 1) / len; }
+    int most = kMaxCols * kMaxSplits / ncols;           // the partials buffer holds kMaxCols * kMaxSplits (column, split) pairs
+    if (most > kMaxSplits) most = kMaxSplits;
+    if (most < 1) most = 1;                             // a single split writes its result directly, no partials
+    if (n > most) { len = ((ctx + most - 1) / most + 63) / 64 * 64; n = (ctx + len - 1) / len; }
     *split_len = len;
     *n_splits = n;
 }
@@ -561,7 +571,8 @@ int prefill_impl(d3_ctx* ctx, const int32_t* tokens, int32_t B, int32_t P, int32
         // row once per tile of queries instead of once per query
         // the matrix-core path takes 128 columns a pass (the weights are streamed once per pass); D3_PREFILL_COLS=64 halves that
         // (projections of large matrices split such a pass into two launches of 64 columns by themselves)
-        const int wide_cols = ctx->tn.prefill_cols ? ctx->tn.prefill_cols : kPassCols;
+        const int fit = pass_cols(d);
+        const int wide_cols = ctx->tn.prefill_cols && ctx->tn.prefill_cols < fit ? ctx->tn.prefill_cols : fit;
         const int chunk_cols = ctx->mfma_ok && ctx->tn.mfma_wide ? wide_cols : kMaxCols;
         for (int b = 0; b < B; ++b) {
             for (int base = pos_begin == 0 ? ctx->row0[b] : 0; base < P;) {     // padding columns are not computed

@@ -108,10 +108,10 @@ def test_small_bf16_matrix_core_path(B, P):
                                        (SMALL_GQA, 2, 72), (SMALL_GQA, 1, 128), (SMALL_BF16, 2, 50), (SMALL_GQA, 1, 168),
                                        (SMALL_GQA, 1, 136), (SMALL_BF16, 1, 144), (SMALL_GQA, 2, 145)])
 def test_prompt_lengths_that_end_in_every_chunk_width(shape, B, P):
-    # the prompt pass takes one sequence at a time in chunks of up to 128 columns; the chunks here have 24, 97, 81, 80, 72,
-    # 128, 50, 128 + 40, 128 + 8, 128 + 16 and 128 + 17 columns, which ends in each of the projection kernels (packed,
-    # 16-column, and the panel kernel with two, four and eight column tiles) and in both attention paths of a prompt chunk
-    # (per column on the vector ALUs at head_dim 64, query tiles on the matrix cores at 128)
+    # the prompt pass takes one sequence at a time in chunks of up to 1024 columns; the chunks here have 24, 97, 81, 80, 72,
+    # 128, 50, 168, 136, 144 and 145 columns, which ends in each of the projection kernels (packed, 16-column, the panel
+    # kernel with two, four and eight column tiles, and the LDS-tiled kernel with a ragged second column block) and in both
+    # attention paths of a prompt chunk (per column on the vector ALUs at head_dim 64, query tiles on the matrix cores at 128)
     _run(shape, B, P, 4, 0.8, 1, forced_seed=9)
 
 
@@ -122,10 +122,20 @@ def test_wide_prompt_chunks_as_two_launches_of_64_columns(monkeypatch):
     _run(SMALL_BF16, 1, 97, 4, 0.8, 1, forced_seed=9)
 
 
-def test_prompt_chunks_of_64_columns(monkeypatch):
-    # the width the large shapes use (more row groups than compute units), forced here on a small one
-    monkeypatch.setenv("D3_PREFILL_COLS", "64")
-    _run(SMALL_GQA, 2, 150, 4, 0.8, 1, forced_seed=9)
+@pytest.mark.parametrize("cols", [64, 128, 256])
+def test_prompt_chunks_of_a_forced_width(monkeypatch, cols):
+    # a prompt of 700 tokens in chunks of 64 or 128 columns (panel kernel) and of 256 (LDS-tiled kernel: two full chunks
+    # and one of 188 columns, whose second column block is ragged)
+    monkeypatch.setenv("D3_PREFILL_COLS", str(cols))
+    _run(SMALL_GQA, 2, 150 if cols == 64 else 700, 4, 0.8, 1, forced_seed=9)
+
+
+def test_lds_tiled_prompt_kernel_shapes():
+    # rows that do not fill the last row block (d_ffn 1376 = 21.5 blocks of 64 gate/up pairs, vocab 2000), K of 11 and 43
+    # stages, five and a half column blocks; then head_dim 64 (vector-ALU attention per column) with 1100 tokens: a chunk
+    # of 1024 columns and one of 76
+    _run(SMALL_GQA, 1, 700, 3, 0.8, 1, forced_seed=19)
+    _run(SMALL_BF16, 1, 1100, 3, 0.9, 2, forced_seed=19)
 
 
 @pytest.mark.parametrize("B,kv", [(1, "f16"), (3, "f16"), (2, "f32")])

@@ -137,16 +137,24 @@ def yardsticks(dec, torch, dev):
     big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)
     big.zero_()
     out = {}
-    for name, t in (("2 GiB", big), ("1 GiB", cal_src), ("128 MiB", cal_src[: 128 << 20])):
+    # sizes of the 7B shape's matrices beside the large ones: O-projection 32 MiB, down-projection 86 MiB, QKV 96 MiB,
+    # gate/up 172 MiB, lm_head 250 MiB (a launch's fixed costs weigh more the smaller its matrix)
+    sizes = (("2 GiB", 2 << 30), ("1 GiB", 1 << 30), ("250 MiB", 250 << 20), ("172 MiB", 172 << 20), ("96 MiB", 96 << 20),
+             ("86 MiB", 86 << 20), ("32 MiB", 32 << 20))
+    for name, nbytes in sizes:
+        t = big[:nbytes]
         dec.stream_read(t)
         torch.cuda.synchronize()
-        n = 5 if t.numel() >= (1 << 30) else 40
+        # each launch reads a different window of the 2 GiB buffer (as every projection of a step reads different weights:
+        # nothing comes from a cache), launches back to back on the stream
+        n = 5 if nbytes >= (1 << 30) else 40
+        windows = [big[(i * nbytes) % ((2 << 30) - nbytes + 1) // 256 * 256:][:nbytes] for i in range(n)]
         ev0.record()
-        for _ in range(n):
-            dec.stream_read(t)
+        for w in windows:
+            dec.stream_read(w)
         ev1.record()
         torch.cuda.synchronize()
-        out[name] = n * t.numel() / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        out[name] = n * nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del big, cal_src
     return copy_gbps, out
 
@@ -358,6 +366,14 @@ def main() -> int:
                 "avg_launch_us_minus_event_pair": dom["us_minus_event_pair"], "frac_minus_event_pair": dom["frac_minus_event_pair"],
                 "bytes_per_launch": dom["bytes_per_launch"]}
     copy_gbps = m["stream_copy_GBps"]
+    if args.config in ("7b", "7b-long", "7b-ragged"):
+        # each projection against a pure read of a buffer of its matrix's size, launched back to back the same way
+        same_size = {"o": "32 MiB", "down": "86 MiB", "qkv": "96 MiB", "gate_up": "172 MiB", "lm_head": "250 MiB"}
+        for cname, label in same_size.items():
+            k = m["kernels"][cname]
+            if k.get("launches"):
+                k["pure_read_of_its_size_GBps"] = m["stream_read_GBps"][label]
+                k["frac_of_pure_read_of_its_size"] = k["GBps"] / m["stream_read_GBps"][label]
     for r in m["by_alpha"].values():
         r["frac_of_measured_read_rate"] = r["achieved_GBps"] / m["stream_read_GBps"]["2 GiB"]
 

@@ -11,9 +11,12 @@
 // and two or four register sets keep the loads of the next stages in flight while stage t is multiplied; one workgroup
 // barrier per stage.
 //
-// Workgroup order: the column blocks of one row block are 8 apart in the launch order, so they run on the same XCD at the
-// same time and the weight slab that the first one pulls from HBM reaches the others from that XCD's L2: per launch the
-// weights cross the HBM interface about once, whatever the number of columns.
+// Workgroup order: the column blocks of one row block are 8 apart in the launch order, which puts them on one XCD at the
+// same time (workgroups go to the XCDs round-robin), so a weight slab pulled into that XCD's L2 serves all of them.  The
+// activation slabs are shared by the few row blocks resident on an XCD only and are re-read through the fabric by every
+// later one (they fit the 256 MB memory-side cache, not the 4 MB L2): the L2 misses of a 2048-column gate/up launch add up
+// to 3.2 GB, 17 times the weight matrix.  A launch order in chunks of 8 row blocks x 4 column blocks per XCD cut that to
+// 1.9 GB and was slower (its padded grid delays the residual projections: down 402 -> 731 us); not kept.
 //
 // SwiGLU: a workgroup's 128 slab rows are 64 gate rows and the 64 up rows of the same outputs, two tiles of each per
 // wave, so a wave finishes silu(gate) * up from its own accumulators.  Operand layouts, RMSNorm folding (1/rms from the

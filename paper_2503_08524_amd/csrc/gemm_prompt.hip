@@ -1,28 +1,48 @@
 // Tiled GEMM on the matrix cores for the prompt pass, 129..2048 activation columns per launch:
 // out[col][row] = sum_k W[row][k] * x[col][k], bf16 weights, activations x = hi + lo (two bf16 halves).
 //
-// With hundreds of columns the contraction is compute-bound (the prompt pass is the one part of the path that is),
-// so the design is the opposite of the skinny kernels': operands are staged in LDS and re-used from there.  A
-// workgroup of eight waves (4 x 2) owns a tile of 256 weight rows x 128 columns (gate/up: four waves, 128 x 128); each wave
-// 64 x 64 of it, i.e. 4 x 4 MFMA tiles whose accumulators never leave registers.  K is walked in stages of 32: the stage's weight slab
-// (128 rows) and activation slab (128 columns, hi and lo) travel global -> registers -> LDS with coalesced 16-byte
-// pieces (rows of 64 bytes whose four segments are swizzled by the row number, which keeps both the stores and the fragment reads free of bank conflicts);
-// a wave reads 4 weight fragments and 8 activation fragments per stage and issues 32 MFMAs with them.  Two LDS buffers
-// and two or four register sets keep the loads of the next stages in flight while stage t is multiplied; one workgroup
-// barrier per stage.
+// With hundreds of columns the contraction is compute-bound (the prompt pass is the one part of the path that is), so
+// the design is the opposite of the skinny kernels': operands are staged in LDS and re-used from there.  A workgroup
+// owns a tile of 256 weight rows x 128 columns whose accumulators never leave registers, and walks K in stages of 32 (one
+// MFMA k-step): the stage's weight slab (256 rows x 64 bytes) and activation slab (128 columns, hi plane and lo plane)
+// go from global memory straight into LDS with global_load_lds_dwordx4 (16 bytes per lane, lane l of the wave lands at
+// base + 16 l, so one instruction fills sixteen 64-byte slab rows; no staging registers, no ds_write instructions).
+// The four 16-byte segments of a slab row are swizzled by the row number, which keeps the fragment reads free of bank
+// conflicts (sixteen consecutive rows x one segment touch each of the sixteen 16-byte bank groups once); since the
+// direct load fixes where a lane's bytes land, the swizzle is applied on the global side: lane l fetches segment
+// (l % 4) ^ ((l / 16) % 4) of row l / 4 of its sixteen-row block.
+//
+// The LDS pipe delivers 128 bytes per cycle and a 16 x 16 x 32 MFMA takes 16 cycles, so with 64 x 64 per wave (12
+// fragment reads for 32 MFMAs) the reads and writes of a stage occupy LDS for as many cycles as its MFMAs occupy the
+// matrix cores, and any time the two do not overlap is lost.  Two kernels:
+//  * gemm_prompt_w4_kernel (QKV, gate/up): four waves (2 x 2), 128 x 64 per wave = 8 x 4 MFMA tiles (16 fragment reads
+//    for 64 MFMAs: a third fewer LDS bytes per MFMA), two LDS buffers of 32 KB, two workgroups per compute unit whose
+//    stage barriers are independent: one multiplies while the other waits for its loads or reads its fragments.
+//  * gemm_prompt_w8_kernel (the residual projections, whose 256 tiles are one per compute unit): eight waves (4 x 2), 64 x
+//    64 per wave, four LDS buffers, and two sets of fragments in registers: while the MFMAs of stage t run from one set,
+//    the LDS reads of stage t + 1 fill the other.
+// The LDS reads are inline assembly: the compiler orders every LDS read it knows of behind ALL outstanding direct-to-LDS
+// loads, which would drain the prefetch at every stage.  Here the vmcnt / lgkmcnt waits are written out (a wave's loads
+// complete in issue order, NL per stage), and empty asm statements that name the fragments as operands keep the MFMAs
+// behind the waits.  7B shape, 2048 columns: QKV 432 -> 350 us, gate/up 805 -> 660, O 167 -> 158, down 402 -> 382
+// against the version that staged the slabs through registers (global -> VGPR -> ds_write, 64 x 64 per wave, fragments
+// read and multiplied in turns).  Measured with the operands' loads taken out, the stage loop of the eight-wave kernel
+// (LDS reads, MFMAs, barrier) takes 68 % of the full time; the matrix cores alone sustain 2.0 PFLOP/s on this chip
+// (80 % of the nominal peak: the clock drops under MFMA load), 1.8 with the LDS reads of this loop beside them.
 //
 // Workgroup order: the column blocks of one row block are 8 apart in the launch order, which puts them on one XCD at the
 // same time (workgroups go to the XCDs round-robin), so a weight slab pulled into that XCD's L2 serves all of them.  The
 // activation slabs are shared by the few row blocks resident on an XCD only and are re-read through the fabric by every
 // later one (they fit the 256 MB memory-side cache, not the 4 MB L2): the L2 misses of a 2048-column gate/up launch add up
 // to 3.2 GB, 17 times the weight matrix.  A launch order in chunks of 8 row blocks x 4 column blocks per XCD cut that to
-// 1.9 GB and was slower (its padded grid delays the residual projections: down 402 -> 731 us); not kept.
+// 1.9 GB and was slower (its padded grid delays the residual projections); not kept.
 //
-// SwiGLU: a workgroup's 128 slab rows are 64 gate rows and the 64 up rows of the same outputs, two tiles of each per
+// SwiGLU: a workgroup's 256 slab rows are 128 gate rows and the 128 up rows of the same outputs, four tiles of each per
 // wave, so a wave finishes silu(gate) * up from its own accumulators.  Operand layouts, RMSNorm folding (1/rms from the
 // producer's partial sums of squares, x * gain and the sum of squares of the new residual handed to the consumer) and
 // epilogues are those of the skinny matrix-core kernels.
 #include <type_traits>
+#include <utility>
 
 #include "d3_common.h"
 
@@ -32,179 +52,37 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) char lds_char;
+typedef const __attribute__((address_space(1))) void global_cvoid;
 
 constexpr int kBK = 32;                        // k per stage = one MFMA k-step
 constexpr int kPitch = 2 * kBK;                // bytes per staged row: four 16-byte segments, no padding
 constexpr int kTileN = 128;                    // columns of a workgroup tile
 constexpr int kBBytes = 2 * kTileN * kPitch;   // activation slab of a stage: hi plane, lo plane
-// WY waves along the rows (x 2 along the columns).  4: eight waves, tile 256 rows x 128 columns, one workgroup per
-// compute unit; 2: four waves, 128 x 128, two workgroups per compute unit.  The larger tile moves a quarter fewer bytes
-// from L2 and through LDS per MFMA (7B shape, 2048 columns: QKV 458 -> 430 us, O 179 -> 165, down 469 -> 402); the gate/up
-// launch has too few row blocks for it (5.4 rounds of workgroups: 820 -> 871 us) and keeps the smaller one.
+constexpr int kLo = kTileN * kPitch;           // the lo plane follows the hi plane
 
-// RW: 16-row weight tiles per wave.  4: workgroup tile 128 rows x 128 columns, two workgroups per compute unit.  (8, a tile
-// of 256 rows with a third fewer LDS and L2 bytes per MFMA but one workgroup per compute unit, was measured 18 % slower:
-// the kernel is bound by the latencies that a second resident workgroup hides, not by LDS bandwidth.)
+// RW: 16-row weight tiles per wave; WY waves along the rows (x 2 along the columns).
 template <int RW, int WY> struct PromptTile {
     static constexpr int kThreads = WY * 2 * 64;
-    static constexpr int kBLoads = 2 * kTileN * 4 / kThreads;   // 16-byte pieces of the activation slab per thread and stage
-    static constexpr int kTileM = 16 * RW * WY;             // slab rows
+    static constexpr int kWaves = WY * 2;
+    static constexpr int kTileM = 16 * RW * WY;             // slab rows (256 in both kernels)
     static constexpr int kABytes = kTileM * kPitch;         // weight slab of a stage
-    static constexpr int kStage = kABytes + kBBytes;        // 30720 or 40960 bytes
-    static constexpr int kALoads = kTileM * 4 / kThreads;   // 16-byte pieces of the weight slab per thread and stage
-    static constexpr int kLds = 2 * kStage;
+    static constexpr int kStage = kABytes + kBBytes;        // 32 KB
+    static constexpr int kBlocks = kStage / 1024;           // sixteen-row blocks of a stage: weights first, then activations hi, lo
+    static constexpr int NL = kBlocks / kWaves;             // direct loads per wave and stage
+    static constexpr int kAJ = kTileM / 16 / kWaves;        // the first kAJ of them fetch weight rows
+    static_assert(kBlocks % kWaves == 0 && (kTileM / 16) % kWaves == 0 && RW % 2 == 0, "slab blocks divide evenly over the waves");
 };
 
-extern __shared__ __attribute__((aligned(16))) char prompt_lds[];
-
+// The epilogue of both kernels, from the accumulators: lane (i, g) holds column i of a column tile, rows 4g..4g+3 of each tile.
 template <int MODE, int RW, int WY>
-__global__ __launch_bounds__(WY * 128, 2) void gemm_prompt_kernel(GemvArgs a, int n_rb, int n_cb) {
-    typedef PromptTile<RW, WY> Tile;
+__device__ __forceinline__ void prompt_epilogue(const GemvArgs& a, f32x4 (&acc)[RW][4], int rb, int cb, int tiles,
+                                                const float* inv_rms, float (*ssq_w)[kTileN]) {
     constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;
-    constexpr int kWavesY = WY, kThreads = Tile::kThreads, kBLoads = Tile::kBLoads;
-    constexpr int OT = kWavesY * RW / SW;              // output row tiles per workgroup (half as many gate/up pairs)
-    constexpr int kABytes = Tile::kABytes, kStage = Tile::kStage, kALoads = Tile::kALoads;
-    struct StageRegs { u32x4 a[kALoads], b[kBLoads]; };
-    char* lds = prompt_lds;
-    __shared__ float inv_rms[kTileN];
-    __shared__ float ssq_w[kWavesY][kTileN];
+    constexpr int kWavesY = WY, OT = WY * RW / SW;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wy = wave >> 1, wx = wave & 1;
     const int li = lane & 15, lg = lane >> 4;
-    // launch order -> (row block, column block): ids 8m .. 8m + 7 are eight row blocks of one column block, the next
-    // eight ids the same row blocks of the next column block
-    const int per_group = 8 * n_cb;
-    const int rb = (blockIdx.x / per_group) * 8 + (blockIdx.x % per_group) % 8;
-    const int cb = (blockIdx.x % per_group) / 8;
-    if (rb >= n_rb) return;
-    const int K = a.K, n_stages = K / kBK;
-    const int tiles = a.total_rows / 16;               // output row tiles of the whole matrix
-
-    // slab row -> weight row.  Slab tile st (0 .. 2 RW - 1): wave wy owns st = RW wy .. RW wy + RW - 1.  Plain modes:
-    // output tile OT rb + st.  SwiGLU: the first RW / 2 tiles of a wave are gate rows, the others the up rows of the same
-    // outputs OT rb + (RW / 2) wy + (st % (RW / 2)).
-    auto slab_row = [&](int s) -> const bf16_t* {
-        const int st = s >> 4, i = s & 15;
-        if (MODE == MODE_SWIGLU) {
-            const int t = st % RW;
-            int otile = rb * OT + (st / RW) * (RW / 2) + t % (RW / 2);
-            otile = otile < tiles ? otile : tiles - 1;  // past the matrix: re-read the last tile (result dropped)
-            return static_cast<const bf16_t*>(a.w[t / (RW / 2)]) + (size_t)(otile * 16 + i) * K;
-        }
-        int otile = rb * OT + st;
-        otile = otile < tiles ? otile : tiles - 1;
-        int m = 0, local = otile * 16;
-        if (local >= a.rows[0]) { local -= a.rows[0]; m = 1; if (local >= a.rows[1]) { local -= a.rows[1]; m = 2; } }
-        return static_cast<const bf16_t*>(a.w[m]) + (size_t)(local + i) * K;
-    };
-    // this thread's pieces: slab row (tid / 4) + (kThreads / 4) j, 16-byte segment tid % 4 (four neighbouring lanes fetch 64 contiguous bytes)
-    constexpr int kRowsPerPass = kThreads / 4;
-    const int prow = tid >> 2, pseg = tid & 3;
-    const bf16_t* asrc[kALoads];
-    const bf16_t* bsrc[kBLoads];
-#pragma unroll
-    for (int j = 0; j < kALoads; ++j) asrc[j] = slab_row(prow + kRowsPerPass * j) + pseg * 8;
-#pragma unroll
-    for (int j = 0; j < kBLoads; ++j) {
-        const int brow = prow + kRowsPerPass * j, plane = brow >> 7, col = cb * kTileN + (brow & 127);
-        bsrc[j] = (plane ? a.x_lo : a.x_hi) + (size_t)col * a.x_stride + pseg * 8;
-    }
-    // Segment s of slab row r sits at slot s ^ ((r / 4) % 4) of the row.  A store instruction's sixteen-lane groups are
-    // four consecutive rows x four segments, a fragment read's are sixteen consecutive rows x one segment: under this
-    // swizzle both touch each of the sixteen 16-byte bank groups once (a padded pitch of 80 keeps the reads conflict-free
-    // but puts rows 0 and 3 of a store group on the same banks: half of the LDS cycles were conflict cycles).
-    const int pdst = prow * kPitch + ((pseg ^ ((prow >> 2) & 3)) << 4);
-
-    auto issue = [&](StageRegs& r, int t) {
-        const int k = t * kBK;
-#pragma unroll
-        for (int j = 0; j < kALoads; ++j) r.a[j] = *reinterpret_cast<const u32x4*>(asrc[j] + k);
-#pragma unroll
-        for (int j = 0; j < kBLoads; ++j) r.b[j] = *reinterpret_cast<const u32x4*>(bsrc[j] + k);
-    };
-    auto store = [&](const StageRegs& r, int buf) {
-        char* base = lds + buf * kStage;
-#pragma unroll
-        for (int j = 0; j < kALoads; ++j) *reinterpret_cast<u32x4*>(base + pdst + kRowsPerPass * j * kPitch) = r.a[j];
-#pragma unroll
-        for (int j = 0; j < kBLoads; ++j) *reinterpret_cast<u32x4*>(base + kABytes + pdst + kRowsPerPass * j * kPitch) = r.b[j];
-    };
-
-    f32x4 acc[RW][4];                                  // [slab tile of the wave][column tile of the wave]
-#pragma unroll
-    for (int r = 0; r < RW; ++r)
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto multiply = [&](int buf) {
-        const int slot = (lg ^ ((li >> 2) & 3)) << 4;      // tile bases are multiples of 16 rows: the swizzle depends on li alone
-        const char* A = lds + buf * kStage + (wy * 16 * RW + li) * kPitch + slot;
-        const char* B = lds + buf * kStage + kABytes + (wx * 64 + li) * kPitch + slot;
-        bf16x8 af[RW];
-#pragma unroll
-        for (int r = 0; r < RW; ++r) af[r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(A + r * 16 * kPitch));
-#pragma unroll
-        for (int tt = 0; tt < 4; ++tt) {
-            const bf16x8 bh = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(B + tt * 16 * kPitch));
-            const bf16x8 bl = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(B + (kTileN + tt * 16) * kPitch));
-#pragma unroll
-            for (int r = 0; r < RW; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[r], bh, acc[r][tt], 0, 0, 0);
-#pragma unroll
-            for (int r = 0; r < RW; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[r], bl, acc[r][tt], 0, 0, 0);
-        }
-    };
-
-    // ---- the stages: LDS holds stages t and t + 1, registers the loads of the stages after them ----
-    // A weight or activation row advances 64 bytes per stage, half a cache line: the loads of stages 2m and 2m + 1 are
-    // issued together, so that the line is fetched into the compute unit's L1 once (issued a stage apart, the second half
-    // found the line evicted and fetched it again: twice the L2 -> L1 traffic, which was what bounded the kernel).
-    // Four register sets (stages t + 1 .. t + 4) for the projections that stream large matrices; two for the residual
-    // projections, whose epilogue (old residual, next gains) leaves the register allocator no room for more.  Past the
-    // last stage the loads re-read it and the store fills a buffer that nobody reads: the steady state has no branch.
-    constexpr int NR = MODE == MODE_RESID ? 2 : 4;
-    StageRegs ra, rb_, rc, rd;
-    const int last = n_stages - 1;
-    auto at = [&](int t) { return t < last ? t : last; };
-    issue(ra, 0);
-    issue(rb_, at(1));
-    if (NR == 4) { issue(rc, at(2)); issue(rd, at(3)); }
-    // 16 threads add up one column's partial sums of squares, in a fixed order
-    if (MODE != MODE_RESID && a.ssq_in) {
-        for (int c = tid >> 4; c < kTileN; c += kThreads / 16) {
-            const int col = cb * kTileN + c;
-            float ss = 0.f;
-            if (col < a.ncols) {
-                const float* p = a.ssq_in + (size_t)col * kSsqStride;
-                for (int i0 = tid & 15; i0 < a.ssq_parts; i0 += 16) ss += p[i0];
-            }
-#pragma unroll
-            for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
-            if ((tid & 15) == 0) inv_rms[c] = 1.0f / sqrtf(ss / (float)K + a.eps);
-        }
-    }
-    store(ra, 0);
-    __syncthreads();
-    // every __syncthreads below: the stage just stored is complete in LDS, and nobody still reads the one just multiplied
-    if constexpr (NR == 4) {
-        for (int t = 0; t < n_stages; t += 4) {
-            multiply(0); store(rb_, 1); issue(ra, at(t + 4)); issue(rb_, at(t + 5)); __syncthreads();
-            if (t + 1 >= n_stages) break;
-            multiply(1); store(rc, 0); __syncthreads();
-            if (t + 2 >= n_stages) break;
-            multiply(0); store(rd, 1); issue(rc, at(t + 6)); issue(rd, at(t + 7)); __syncthreads();
-            if (t + 3 >= n_stages) break;
-            multiply(1); store(ra, 0); __syncthreads();
-        }
-    } else {
-        for (int t = 0; t < n_stages; t += 2) {
-            multiply(0); store(rb_, 1); issue(ra, at(t + 2)); issue(rb_, at(t + 3)); __syncthreads();
-            if (t + 1 >= n_stages) break;
-            multiply(1); store(ra, 0); __syncthreads();
-        }
-    }
-
-    asm volatile("" ::: "memory");                     // the epilogue's loads stay behind the last stage
-    // ---- epilogue from the accumulators: lane (i, g) holds column i of a column tile, rows 4g..4g+3 of each tile ----
     float sq[4];
 #pragma unroll
     for (int tt = 0; tt < 4; ++tt) sq[tt] = 0.f;
@@ -275,17 +153,269 @@ __global__ __launch_bounds__(WY * 128, 2) void gemm_prompt_kernel(GemvArgs a, in
     }
 }
 
+extern __shared__ __attribute__((aligned(16))) char prompt_lds[];
+
+template <int OFF>
+__device__ __forceinline__ bf16x8 lds_read_frag(uint32_t addr) {
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+    return __builtin_bit_cast(bf16x8, v);
+}
+template <int N> __device__ __forceinline__ void vm_loads_left() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
+template <int N> __device__ __forceinline__ void lds_reads_left() { asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(N) : "memory"); }
+// Nothing that uses the fragment moves above this statement, and volatile statements keep their order: after a wait it
+// keeps the MFMAs behind the wait; after the reads of the next stage it keeps this stage's MFMAs behind those reads.
+__device__ __forceinline__ void pin_frag(bf16x8& v) { asm volatile("" : "+v"(v)); }
+
+template <int RW> struct PromptFrags { bf16x8 a[RW], bh[4], bl[4]; };
+template <int RW, int... R>
+__device__ __forceinline__ void read_a_frags(PromptFrags<RW>& f, uint32_t A, std::integer_sequence<int, R...>) {
+    ((f.a[R] = lds_read_frag<R * 1024>(A)), ...);
+}
+// all fragments of a stage: weight tiles 0 .. RW - 1, then hi and lo of column tile 0, of column tile 1, ...
+template <int RW>
+__device__ __forceinline__ void read_frags(PromptFrags<RW>& f, uint32_t A, uint32_t B) {
+    read_a_frags<RW>(f, A, std::make_integer_sequence<int, RW>{});
+    f.bh[0] = lds_read_frag<0>(B);      f.bl[0] = lds_read_frag<kLo>(B);
+    f.bh[1] = lds_read_frag<1024>(B);   f.bl[1] = lds_read_frag<kLo + 1024>(B);
+    f.bh[2] = lds_read_frag<2048>(B);   f.bl[2] = lds_read_frag<kLo + 2048>(B);
+    f.bh[3] = lds_read_frag<3072>(B);   f.bl[3] = lds_read_frag<kLo + 3072>(B);
+}
+template <int RW>
+__device__ __forceinline__ void pin_frags(PromptFrags<RW>& f) {
+#pragma unroll
+    for (int r = 0; r < RW; ++r) pin_frag(f.a[r]);
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) { pin_frag(f.bh[tt]); pin_frag(f.bl[tt]); }
+}
+template <int RW>
+__device__ __forceinline__ void mma_column_tile(f32x4 (&acc)[RW][4], const PromptFrags<RW>& f, int tt) {
+#pragma unroll
+    for (int r = 0; r < RW; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[r], f.bh[tt], acc[r][tt], 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < RW; ++r) acc[r][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.a[r], f.bl[tt], acc[r][tt], 0, 0, 0);
+}
+
+// What both kernels do before their stage loops.  Launch order -> (row block, column block): ids 8m .. 8m + 7 are eight
+// row blocks of one column block, the next eight ids the same row blocks of the next column block.
 template <int MODE, int RW, int WY>
-int launch_tile(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
-    auto* k = gemm_prompt_kernel<MODE, RW, WY>;
-    constexpr int lds = PromptTile<RW, WY>::kLds;
-    constexpr int kThreads = PromptTile<RW, WY>::kThreads;
-    if (lds > 48 * 1024) {
-        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (once != hipSuccess) return (int)once;
+struct PromptSetup {
+    typedef PromptTile<RW, WY> Tile;
+    static constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;
+    static constexpr int OT = WY * RW / SW;            // output row tiles per workgroup (half as many gate/up pairs)
+    int rb, cb, tiles;
+    const bf16_t* src[Tile::NL];                       // this lane's piece of each of the wave's sixteen-row blocks, at k = 0
+    uint32_t a_off, b_off;                             // LDS addresses of this lane's first weight / activation fragment in buffer 0
+
+    __device__ __forceinline__ bool init(const GemvArgs& a, int n_rb, int n_cb, int wave, int lane, float* inv_rms) {
+        const int per_group = 8 * n_cb;
+        rb = (blockIdx.x / per_group) * 8 + (blockIdx.x % per_group) % 8;
+        cb = (blockIdx.x % per_group) / 8;
+        if (rb >= n_rb) return false;
+        const int K = a.K;
+        tiles = a.total_rows / 16;                     // output row tiles of the whole matrix
+        // slab row -> weight row.  Slab tile st (0 .. WY RW - 1): wave row wy owns st = RW wy .. RW wy + RW - 1.  Plain modes:
+        // output tile OT rb + st.  SwiGLU: the first RW / 2 tiles of a wave are gate rows, the others the up rows of the same
+        // outputs OT rb + (RW / 2) wy + (st % (RW / 2)).  Tiles past the matrix re-read the last tile (result dropped).
+        auto slab_row = [&](int s) -> const bf16_t* {
+            const int st = s >> 4, i = s & 15;
+            if (MODE == MODE_SWIGLU) {
+                const int t = st % RW;
+                int otile = rb * OT + (st / RW) * (RW / 2) + t % (RW / 2);
+                otile = otile < tiles ? otile : tiles - 1;
+                return static_cast<const bf16_t*>(a.w[t / (RW / 2)]) + (size_t)(otile * 16 + i) * K;
+            }
+            int otile = rb * OT + st;
+            otile = otile < tiles ? otile : tiles - 1;
+            int m = 0, local = otile * 16;
+            if (local >= a.rows[0]) { local -= a.rows[0]; m = 1; if (local >= a.rows[1]) { local -= a.rows[1]; m = 2; } }
+            return static_cast<const bf16_t*>(a.w[m]) + (size_t)(local + i) * K;
+        };
+        const int prow = lane >> 2, pseg = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+        for (int j = 0; j < Tile::NL; ++j) {
+            const int s = 16 * (wave + Tile::kWaves * j) + prow;
+            if (j < Tile::kAJ) src[j] = slab_row(s) + pseg * 8;
+            else {
+                const int b = s - Tile::kTileM, plane = b >> 7, col = cb * kTileN + (b & 127);
+                src[j] = (plane ? a.x_lo : a.x_hi) + (size_t)col * a.x_stride + pseg * 8;
+            }
+        }
+        // fragment reads: lane (i, g) takes segment g of row i of a tile, at slot g ^ ((i / 4) % 4) (tile bases are
+        // multiples of 16 rows, so the swizzle depends on i alone)
+        const int wy = wave >> 1, wx = wave & 1, li = lane & 15, lg = lane >> 4;
+        const uint32_t slot = (uint32_t)((lg ^ ((li >> 2) & 3)) << 4);
+        const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)prompt_lds;
+        a_off = lds0 + (wy * 16 * RW + li) * kPitch + slot;
+        b_off = lds0 + Tile::kABytes + (wx * 64 + li) * kPitch + slot;
+        // 16 threads add up one column's partial sums of squares, in a fixed order (before the direct loads: vmcnt counts these loads too)
+        if (MODE != MODE_RESID && a.ssq_in) {
+            const int tid = threadIdx.x;
+            for (int c = tid >> 4; c < kTileN; c += Tile::kThreads / 16) {
+                const int col = cb * kTileN + c;
+                float ss = 0.f;
+                if (col < a.ncols) {
+                    const float* p = a.ssq_in + (size_t)col * kSsqStride;
+                    for (int i0 = tid & 15; i0 < a.ssq_parts; i0 += 16) ss += p[i0];
+                }
+#pragma unroll
+                for (int o = 8; o >= 1; o >>= 1) ss += __shfl_xor(ss, o, 64);
+                if ((tid & 15) == 0) inv_rms[c] = 1.0f / sqrtf(ss / (float)K + a.eps);
+            }
+        }
+        vm_loads_left<0>();
+        return true;
     }
-    hipLaunchKernelGGL(k, dim3((n_rb + 7) / 8 * 8 * n_cb), dim3(kThreads), lds, s, a, n_rb, n_cb);
+    // stage t -> LDS buffer buf (its 1 KB blocks in slab order; this wave's are wave, wave + kWaves, ...)
+    __device__ __forceinline__ void dma(int t, int buf, int wave) const {
+        lds_char* dst = (lds_char*)prompt_lds + buf * Tile::kStage + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < Tile::NL; ++j)
+            __builtin_amdgcn_global_load_lds((global_cvoid*)(src[j] + (size_t)t * kBK),
+                                             (__attribute__((address_space(3))) void*)(dst + j * Tile::kWaves * 1024), 16, 0, 0);
+    }
+};
+
+// ---------------- four waves, 128 x 64 per wave, two workgroups per compute unit ----------------
+// One set of fragments, two LDS buffers.  Stage t: wait for the wave's own loads of the stage, barrier (everybody's have
+// landed, nobody still reads stage t - 1), request stage t + 1 into the other buffer, read the 16 fragments, and
+// multiply column tile by column tile as its fragments arrive.
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void gemm_prompt_w4_kernel(GemvArgs a, int n_rb, int n_cb) {
+    constexpr int RW = 8, WY = 2;
+    typedef PromptTile<RW, WY> Tile;
+    __shared__ float inv_rms[kTileN];
+    __shared__ float ssq_w[WY][kTileN];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    PromptSetup<MODE, RW, WY> su;
+    if (!su.init(a, n_rb, n_cb, wave, lane, inv_rms)) return;
+    const int n_stages = a.K / kBK;
+    su.dma(0, 0, wave);
+
+    f32x4 acc[RW][4];                                  // [slab tile of the wave][column tile of the wave]
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    PromptFrags<RW> f;
+    for (int t = 0; t < n_stages; ++t) {
+        vm_loads_left<0>();                            // this wave's part of stage t has landed ...
+        __syncthreads();                               // ... and everybody's; nobody still reads stage t - 1 (and inv_rms is written)
+        if (t + 1 < n_stages) su.dma(t + 1, (t + 1) & 1, wave);
+        read_frags<RW>(f, su.a_off + (t & 1) * Tile::kStage, su.b_off + (t & 1) * Tile::kStage);
+        lds_reads_left<6>();                           // the weight tiles and column tile 0
+#pragma unroll
+        for (int r = 0; r < RW; ++r) pin_frag(f.a[r]);
+        pin_frag(f.bh[0]); pin_frag(f.bl[0]);
+        mma_column_tile<RW>(acc, f, 0);
+        __builtin_amdgcn_sched_barrier(0);             // the scheduler moves nothing across: the next wait stays behind these MFMAs
+        lds_reads_left<4>();
+        pin_frag(f.bh[1]); pin_frag(f.bl[1]);
+        mma_column_tile<RW>(acc, f, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_reads_left<2>();
+        pin_frag(f.bh[2]); pin_frag(f.bl[2]);
+        mma_column_tile<RW>(acc, f, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_reads_left<0>();
+        pin_frag(f.bh[3]); pin_frag(f.bl[3]);
+        mma_column_tile<RW>(acc, f, 3);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    asm volatile("" ::: "memory");                     // the epilogue's loads stay behind the last stage
+    prompt_epilogue<MODE, RW, WY>(a, acc, su.rb, su.cb, su.tiles, inv_rms, ssq_w);
+}
+
+// ---------------- eight waves, 64 x 64 per wave, fragments double-buffered in registers ----------------
+// Four LDS buffers: stage t + 1 is being read, t + 2 .. t + 4 are in flight or landed.  Stage t: the fragments of stage
+// t are in registers (read during stage t - 1).  Loads are issued in the order 0 1 2 3 | 4 5 (at stage 1) | 6 7 (at stage
+// 3) | ...: the two stages of a pair are the two halves of the rows' cache lines, requested together so that a line is
+// fetched into the compute unit's L1 once.  When stage t + 1 must have landed, the stages issued after it are t + 2, t + 3
+// (t even) or t + 2 (t odd).  The steady state has no branch; the last four stages issue nothing and wait for everything.
+// Needs an even number of stages, at least four.
+template <int MODE>
+__global__ __launch_bounds__(512, 2) void gemm_prompt_w8_kernel(GemvArgs a, int n_rb, int n_cb) {
+    constexpr int RW = 4, WY = 4, NB = 4;
+    typedef PromptTile<RW, WY> Tile;
+    constexpr int NL = Tile::NL, kStage = Tile::kStage;
+    static_assert(3 * NL < 64, "vmcnt holds 6 bits");
+    __shared__ float inv_rms[kTileN];
+    __shared__ float ssq_w[WY][kTileN];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    PromptSetup<MODE, RW, WY> su;
+    if (!su.init(a, n_rb, n_cb, wave, lane, inv_rms)) return;
+    const int n_stages = a.K / kBK;
+    su.dma(0, 0, wave); su.dma(1, 1, wave); su.dma(2, 2, wave); su.dma(3, 3, wave);
+
+    f32x4 acc[RW][4];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto read = [&](PromptFrags<RW>& f, int t) { read_frags<RW>(f, su.a_off + (t & (NB - 1)) * kStage, su.b_off + (t & (NB - 1)) * kStage); };
+    // the reads of the next stage are in flight while this stage's MFMAs run, and the MFMAs stay above the next stage's waits
+    auto mma = [&](PromptFrags<RW>& f) {
+        pin_frags<RW>(f);
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) mma_column_tile<RW>(acc, f, tt);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    PromptFrags<RW> f0, f1;
+    vm_loads_left<3 * NL>();
+    __syncthreads();                                   // stage 0 is in LDS (and inv_rms is written)
+    read(f0, 0);
+    int t = 0;
+    for (; t + 4 < n_stages; t += 2) {
+        vm_loads_left<2 * NL>();
+        lds_reads_left<0>();
+        __syncthreads();                               // stage t + 1 is complete in LDS; nobody still reads stages <= t
+        read(f1, t + 1);
+        mma(f0);
+        vm_loads_left<NL>();
+        lds_reads_left<0>();
+        __syncthreads();
+        su.dma(t + 4, t & (NB - 1), wave); su.dma(t + 5, (t + 1) & (NB - 1), wave);
+        read(f0, t + 2);
+        mma(f1);
+    }
+    // t = n_stages - 4
+    vm_loads_left<0>();
+    lds_reads_left<0>();
+    __syncthreads();
+    read(f1, t + 1);
+    mma(f0);
+    lds_reads_left<0>();
+    __syncthreads();
+    read(f0, t + 2);
+    mma(f1);
+    lds_reads_left<0>();
+    __syncthreads();
+    read(f1, t + 3);
+    mma(f0);
+    lds_reads_left<0>();
+    mma(f1);
+    asm volatile("" ::: "memory");
+    prompt_epilogue<MODE, RW, WY>(a, acc, su.rb, su.cb, su.tiles, inv_rms, ssq_w);
+}
+
+template <typename Kern>
+int launch_prompt(Kern* k, int threads, int lds, const GemvArgs& a, int n_rb, int n_cb, hipStream_t s, hipError_t attr) {
+    if (attr != hipSuccess) return (int)attr;
+    hipLaunchKernelGGL(k, dim3((n_rb + 7) / 8 * 8 * n_cb), dim3(threads), lds, s, a, n_rb, n_cb);
     return (int)hipGetLastError();
+}
+template <int MODE>
+int launch_w4(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
+    constexpr int lds = 2 * PromptTile<8, 2>::kStage;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prompt_w4_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return launch_prompt(gemm_prompt_w4_kernel<MODE>, 256, lds, a, n_rb, n_cb, s, attr);
+}
+int launch_w8_resid(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
+    constexpr int lds = 4 * PromptTile<4, 4>::kStage;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prompt_w8_kernel<MODE_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    return launch_prompt(gemm_prompt_w8_kernel<MODE_RESID>, 512, lds, a, n_rb, n_cb, s, attr);
 }
 
 }  // namespace
@@ -294,18 +424,17 @@ int launch_tile(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
 // kPassCols (x_hi / x_lo hold ncols rounded up to 128 rows); with ssq_out at most kSsqStride row blocks.
 int launch_gemm_prompt(const GemvArgs& a, int mode, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
-    const int sw = mode == MODE_SWIGLU ? 2 : 1;
     const int n_cb = (a.ncols + kTileN - 1) / kTileN;
-    if (a.ncols < 1 || a.ncols > kPassCols || a.K % kBK != 0) return (int)hipErrorInvalidValue;
-    constexpr int rw = 4;
-    const int wy = mode == MODE_SWIGLU ? 2 : 4;
-    const int ot = wy * rw / sw;
+    if (a.ncols < 1 || a.ncols > kPassCols || a.K % kBK != 0 || a.K < kBK) return (int)hipErrorInvalidValue;
+    const int ot = mode == MODE_SWIGLU ? 8 : 16;       // output row tiles per workgroup: 256 slab rows in both kernels
     const int n_rb = (tiles + ot - 1) / ot;
     if (a.ssq_out && n_rb > kSsqStride) return (int)hipErrorInvalidValue;
     if (n_groups) *n_groups = n_rb;
-    if (mode == MODE_STORE) return launch_tile<MODE_STORE, rw, 4>(a, n_rb, n_cb, s);
-    if (mode == MODE_RESID) return launch_tile<MODE_RESID, rw, 4>(a, n_rb, n_cb, s);
-    return launch_tile<MODE_SWIGLU, rw, 2>(a, n_rb, n_cb, s);
+    const int n_stages = a.K / kBK;
+    if (mode == MODE_STORE) return launch_w4<MODE_STORE>(a, n_rb, n_cb, s);
+    if (mode == MODE_SWIGLU) return launch_w4<MODE_SWIGLU>(a, n_rb, n_cb, s);
+    if (n_stages >= 4 && n_stages % 2 == 0) return launch_w8_resid(a, n_rb, n_cb, s);
+    return launch_w4<MODE_RESID>(a, n_rb, n_cb, s);
 }
 
 }  // namespace d3

@@ -205,6 +205,24 @@ def measure_config(name, steps, warmup, fill, kv_arg=None, with_yardsticks=False
                       "frac_algorithmic": flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                       "frac_issued": 2 * flops / prefill_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
+    if with_yardsticks:
+        # what the matrix cores sustain on this chip: the stage loop of the prompt GEMM on fixed operands (d3_mfma_yardstick)
+        n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+        sustained = {}
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for mode, label in ((0, "mfma_alone"), (1, "with_lds_fragment_reads"), (2, "with_reads_and_stage_barrier")):
+            dec.mfma_yardstick(mode, 1024)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(3):
+                dec.mfma_yardstick(mode, 4096)
+            e1.record()
+            torch.cuda.synchronize()
+            sustained[label] = 3 * n_cu * 8 * 4096 * 32 * 16384 / (e0.elapsed_time(e1) * 1e-3) / 1e12
+        res["prefill"]["sustained_TFLOPs"] = sustained
+        res["prefill"]["frac_issued_of_sustained_mfma_alone"] = res["prefill"]["issued_TFLOPs_hi_lo"] / sustained["mfma_alone"]
+        progress(f"{name}: matrix cores sustain {sustained['mfma_alone']:.0f} TFLOP/s alone, {sustained['with_reads_and_stage_barrier']:.0f} in the prompt GEMM's stage loop")
+
     kv_bytes = 4 if kv == "f32" else 2
     results = {}
     for alpha in alphas:

@@ -240,6 +240,14 @@ int d3_profile_read(d3_ctx *ctx, double *total_ms, int64_t *launches);
  * against).  Asynchronous on the given stream; the checksum lands in the context's workspace. */
 int d3_stream_read(d3_ctx *ctx, const void *src, size_t bytes, void *hip_stream);
 
+/* Measurement aid for the prompt pass (Section 3.2: the first token runs every block; the one compute-bound part of the
+ * path): one launch of one workgroup per compute unit that runs the stage loop of the prompt-pass GEMM on fixed
+ * operands, 8 waves x `stages` x 32 matrix-core instructions of 16384 flops per workgroup, and touches no global memory
+ * but one word per wave.  mode 0: the matrix-core instructions alone; 1: with the loop's LDS fragment reads beside
+ * them; 2: with its workgroup barrier per stage as well.  `stages` even, in [2, 2^20].  Asynchronous on the given
+ * stream; what the matrix cores sustain on this chip is the flop count over the launch's duration. */
+int d3_mfma_yardstick(d3_ctx *ctx, int32_t mode, int32_t stages, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

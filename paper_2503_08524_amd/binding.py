@@ -76,6 +76,7 @@ def load_library() -> C.CDLL:
         lib.d3_n_ctx.restype = i32
         lib.d3_truncate.argtypes = [vp, i32]
         lib.d3_stream_read.argtypes = [vp, vp, C.c_size_t, vp]
+        lib.d3_mfma_yardstick.argtypes = [vp, i32, i32, vp]
         lib.d3_profile_select.argtypes = [vp, i32]
         lib.d3_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         _LIB = lib
@@ -245,6 +246,11 @@ class Decoder:
     def stream_read(self, tensor) -> None:
         """Read-only streaming yardstick over a CUDA tensor (one launch, asynchronous)."""
         _check(self.lib.d3_stream_read(self.ctx, tensor.data_ptr(), tensor.numel() * tensor.element_size(), self._stream()))
+
+    def mfma_yardstick(self, mode: int, stages: int) -> None:
+        """Matrix-core yardstick of the prompt pass (one launch, asynchronous): mode 0 MFMAs alone, 1 with the stage loop's
+        LDS reads, 2 with its barrier too; n_cu workgroups x 8 waves x stages x 32 instructions of 16384 flops."""
+        _check(self.lib.d3_mfma_yardstick(self.ctx, mode, stages, self._stream()))
 
     def profile_select(self, kernel_class: int) -> None:
         _check(self.lib.d3_profile_select(self.ctx, kernel_class))

@@ -794,6 +794,16 @@ extern "C" int d3_stream_read(d3_ctx* ctx, const void* src, size_t bytes, void* 
     return D3_OK;
 }
 
+extern "C" int d3_mfma_yardstick(d3_ctx* ctx, int32_t mode, int32_t stages, void* hip_stream) {
+    if (!ctx) return fail(D3_EINVAL, "d3_mfma_yardstick: ctx is NULL");
+    if (mode < 0 || mode > 2 || stages < 2 || stages > (1 << 20) || stages % 2 != 0)
+        return fail(D3_EINVAL, "d3_mfma_yardstick: mode must be 0, 1 or 2 and stages even, in [2, 2^20] (got %d, %d)", mode, stages);
+    // one workgroup of eight waves per compute unit, like the residual projections of the prompt pass; a word per wave lands in the attention partials
+    if ((size_t)ctx->n_cu * 8 * sizeof(float) > ctx->lay.part_ml - ctx->lay.part_o) return fail(D3_ESHAPE, "d3_mfma_yardstick: the workspace of this model is too small for the result words");
+    D3_HIP(launch_mfma_yardstick(mode, stages, ctx->n_cu, ctx->at<float>(ctx->lay.part_o), static_cast<hipStream_t>(hip_stream)));
+    return D3_OK;
+}
+
 extern "C" int d3_profile_select(d3_ctx* ctx, int32_t kernel_class) {
     if (!ctx) return fail(D3_EINVAL, "d3_profile_select: ctx is NULL");
     if (kernel_class < D3_K_NONE || kernel_class > D3_K_EMPTY) return fail(D3_EINVAL, "d3_profile_select: unknown class %d", kernel_class);

@@ -190,6 +190,7 @@ int launch_fill(const FillArgs& a, int kv_dtype, hipStream_t s);
 
 // read-only streaming yardstick: reads `bytes` (a multiple of 16) once; sink: n_wg * 4 words
 int launch_stream_read(const void* src, size_t bytes, unsigned* sink, int n_wg, hipStream_t s);
+int launch_mfma_yardstick(int mode, int stages, int n_wg, float* sink, hipStream_t s);   // gemm_prompt.hip
 
 // The words of state a decode step expects in its scratch area, passed by value (no host buffer to copy from) and
 // written by one small kernel, which also zeroes the arrival counters.

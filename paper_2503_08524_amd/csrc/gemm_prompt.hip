@@ -400,6 +400,52 @@ __global__ __launch_bounds__(512, 2) void gemm_prompt_w8_kernel(GemvArgs a, int 
     prompt_epilogue<MODE, RW, WY>(a, acc, su.rb, su.cb, su.tiles, inv_rms, ssq_w);
 }
 
+// ---------------- yardstick: what the matrix cores sustain with this file's stage loop ----------------
+// The stage loop of the eight-wave kernel without its operands' loads: 32 MFMAs per wave and stage on fragments that
+// (mode >= 1) are re-read from a fixed LDS buffer every stage as in the kernel, (mode 2) with the stage barrier.  One
+// workgroup per launched block, no global memory traffic but one word per wave at the end.
+template <int V>
+__global__ __launch_bounds__(512, 2) void mfma_yardstick_kernel(float* __restrict__ sink, int stages) {
+    constexpr int RW = 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, li = lane & 15, lg = lane >> 4;
+    unsigned* words = reinterpret_cast<unsigned*>(prompt_lds);
+    for (int i = tid; i < PromptTile<4, 4>::kStage / 4; i += 512) words[i] = 0x3c003c00u ^ ((unsigned)i * 2654435761u & 0x00ff00ffu);   // bf16 values near 1
+    __syncthreads();
+    const uint32_t slot = (uint32_t)((lg ^ ((li >> 2) & 3)) << 4);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)prompt_lds;
+    const uint32_t A = lds0 + ((wave >> 1) * 16 * RW + li) * kPitch + slot, B = lds0 + PromptTile<4, 4>::kABytes + ((wave & 1) * 64 + li) * kPitch + slot;
+    f32x4 acc[RW][4];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    PromptFrags<RW> f0, f1;
+    read_frags<RW>(f0, A, B);
+    lds_reads_left<0>();
+    pin_frags<RW>(f0);
+    f1 = f0;
+    auto half = [&](PromptFrags<RW>& cur, PromptFrags<RW>& nxt) {
+        if (V >= 1) lds_reads_left<0>();
+        if (V >= 2) __syncthreads();
+        if (V >= 1) read_frags<RW>(nxt, A, B);
+        pin_frags<RW>(cur);
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) mma_column_tile<RW>(acc, cur, tt);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int t = 0; t < stages; t += 2) { half(f0, f1); half(f1, f0); }
+    lds_reads_left<0>();
+    pin_frags<RW>(f0);
+    float sum = (float)f0.a[0][0];
+#pragma unroll
+    for (int r = 0; r < RW; ++r)
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) sum += acc[r][tt][0] + acc[r][tt][3];
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (lane == 0) sink[blockIdx.x * 8 + wave] = sum;
+}
+
 template <typename Kern>
 int launch_prompt(Kern* k, int threads, int lds, const GemvArgs& a, int n_rb, int n_cb, hipStream_t s, hipError_t attr) {
     if (attr != hipSuccess) return (int)attr;
@@ -435,6 +481,17 @@ int launch_gemm_prompt(const GemvArgs& a, int mode, hipStream_t s, int* n_groups
     if (mode == MODE_SWIGLU) return launch_w4<MODE_SWIGLU>(a, n_rb, n_cb, s);
     if (n_stages >= 4 && n_stages % 2 == 0) return launch_w8_resid(a, n_rb, n_cb, s);
     return launch_w4<MODE_RESID>(a, n_rb, n_cb, s);
+}
+
+// mode 0: MFMAs alone; 1: with the fragment reads of the stage loop; 2: with the stage barrier as well.  n_wg workgroups of
+// eight waves; sink holds 8 floats per workgroup.  Flops issued: n_wg * 8 waves * stages * 32 MFMAs * 16384.
+int launch_mfma_yardstick(int mode, int stages, int n_wg, float* sink, hipStream_t s) {
+    constexpr int lds = PromptTile<4, 4>::kStage;
+    if (mode < 0 || mode > 2 || stages < 2 || stages % 2 != 0) return (int)hipErrorInvalidValue;
+    if (mode == 0) hipLaunchKernelGGL(mfma_yardstick_kernel<0>, dim3(n_wg), dim3(512), lds, s, sink, stages);
+    else if (mode == 1) hipLaunchKernelGGL(mfma_yardstick_kernel<1>, dim3(n_wg), dim3(512), lds, s, sink, stages);
+    else hipLaunchKernelGGL(mfma_yardstick_kernel<2>, dim3(n_wg), dim3(512), lds, s, sink, stages);
+    return (int)hipGetLastError();
 }
 
 }  // namespace d3

@@ -375,3 +375,26 @@ def test_continuation_prompt_whose_query_tiles_straddle_an_attention_split(P2):
         gens2.append(oracle.generate(model, prompts2[b], G2, alpha, start, seq=gen.seq, pos_begin=n_rows, forced=forced2[b]))
     wl, wh = helpers.compare(gpu2, gens2, G2)
     print(f"  worst logit abs err {wl:.3e}, hidden {wh:.3e}", flush=True)
+
+
+def test_measurement_aids_run_and_check_their_arguments():
+    # the read-only stream and the matrix-core yardstick that bench.py holds its rates against: every mode runs to the
+    # end on a small model's workspace, bad arguments are refused before anything is launched
+    import torch
+    from paper_2503_08524_amd import binding, D3Error
+    shape = SHAPE
+    w = binding.weights_to_device(shape, d3_inputs.make_weights(shape, 2))
+    dec = binding.Decoder(shape, w, 1, 16)
+    for mode in (0, 1, 2):
+        dec.mfma_yardstick(mode, 64)
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+    dec.stream_read(buf)
+    torch.cuda.synchronize()
+    for mode, stages in ((3, 64), (-1, 64), (0, 0), (0, 63), (0, (1 << 20) + 2)):
+        with pytest.raises(D3Error) as e:
+            dec.mfma_yardstick(mode, stages)
+        assert e.value.status == -1
+    with pytest.raises(D3Error) as e:
+        dec.stream_read(buf[1:17])
+    assert e.value.status == -1
+    dec.close()

@@ -131,11 +131,15 @@ def test_prompt_chunks_of_a_forced_width(monkeypatch, cols):
 
 
 def test_lds_tiled_prompt_kernel_shapes():
-    # rows that do not fill the last row block (d_ffn 1376 = 21.5 blocks of 64 gate/up pairs, vocab 2000), K of 11 and 43
-    # stages, five and a half column blocks; then head_dim 64 (vector-ALU attention per column) with 1100 tokens: a chunk
-    # of 1024 columns and one of 76
+    # rows that do not fill the last row block (d_ffn 1376 = 10.75 blocks of 128 gate/up pairs, vocab 2000), five and a half
+    # column blocks; K of 16 stages (four-wave kernel) and 43 stages (odd: the residual projection cannot pair its stages
+    # and takes the four-wave kernel too); then head_dim 64 (vector-ALU attention per column) with 1100 tokens, a chunk of
+    # 1024 columns and one of 76, K of 8 and 22 stages (even: the residual projections run the eight-wave kernel, whose
+    # steady-state loop runs twice and nine times before its four-stage tail)
     _run(SMALL_GQA, 1, 700, 3, 0.8, 1, forced_seed=19)
     _run(SMALL_BF16, 1, 1100, 3, 0.9, 2, forced_seed=19)
+    # the shortest contractions: K of 4 stages (the eight-wave kernel is all prologue and tail) and of 6 (one steady-state turn)
+    _run(ModelShape("narrow", L=2, d=128, H=2, H_kv=1, hd=64, F=192, V=512, dtype="bf16"), 1, 300, 3, 0.9, 1, forced_seed=19)
 
 
 @pytest.mark.parametrize("B,kv", [(1, "f16"), (3, "f16"), (2, "f32")])

@@ -87,3 +87,11 @@ def test_all_40_blocks_13b_batch4_packed_matrix_core_projections():
 @pytest.mark.timeout(900)
 def test_all_80_blocks_70b_batch8_grouped_query_attention():
     _depth_case("llama-70b", 8, 8, 3, sampled=(2, 7))
+
+
+@pytest.mark.timeout(900)
+def test_all_32_blocks_7b_prompt_pass_on_the_lds_tiled_kernels():
+    # a prompt of 144 tokens goes through every block as one chunk of 144 columns: the direct-to-LDS GEMMs (a full column
+    # block and a ragged one of 16 columns; QKV and gate/up on the four-wave kernel, the residual projections on the
+    # eight-wave kernel with K of 128 and 344 stages) and the query-tile attention, at the 7B widths
+    _depth_case("llama-7b", 1, 144, 2, sampled=(0,))

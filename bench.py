@@ -15,7 +15,7 @@ each with its algorithmic HBM bytes per token and fraction of the 8 TB/s peak.
 Beside the headline the line carries: `kernels` (every kernel class of a block at full depth: microseconds per launch
 between HIP events on the launch stream, algorithmic bytes, fraction of the 8 TB/s peak), `roofline` (the dominant
 kernel, same clock), a read-only streaming yardstick (`stream_read`), the prompt pass against the bf16 matrix-core
-peak (`prefill`), and `by_config`: the 13B (batch 4), 7B batch-32 and 70B (batch 8) configurations, each with full
+peak and against what the matrix cores sustain on this chip (`prefill`, `prefill.sustained_TFLOPs`), and `by_config`: the 13B (batch 4), 7B batch-32 and 70B (batch 8) configurations, each with full
 depth and D^3, two timed requests each (skip them with --no-extra-configs).
 
 python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 7b|13b|7b-b32|70b|tiny|7b-long|7b-ragged]

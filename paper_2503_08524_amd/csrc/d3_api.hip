@@ -86,7 +86,7 @@ Layout make_layout(const d3_model_desc& d, size_t C, size_t CS, bool with_gemm_p
     l.n_lo = take(CS * d.d_model * 2);
     l.ssq = take(C * kSsqStride * 4);
     l.h_skip = take(PC * d.d_model * 4);                              // decode passes only
-    l.gemm_part = take(with_gemm_part ? kGemmPartBytes : 0);
+    l.gemm_part = take(with_gemm_part ? (C > 128 ? kPromptPartBytes : kGemmPartBytes) : 0);   // passes of more than 128 columns are prompt chunks
     l.gemm_tickets = take((size_t)kGemmPartTickets * 4);
     l.row0 = take(kMaxCols * 4);
     l.total = o;
@@ -126,6 +126,7 @@ Tuning tuning_from_env() {
     t.attn_min_split = env_int("D3_ATTN_MIN_SPLIT", 64, 65536, 128) / 64 * 64;
     const int pc = env_int("D3_PREFILL_COLS", 64, kPassCols, 0);
     t.prefill_cols = pc % 64 == 0 ? pc : 0;
+    t.prompt_ks = env_int("D3_PROMPT_KS", 1, 4, 0);
     return t;
 }
 }  // namespace d3

@@ -11,6 +11,7 @@ constexpr int kMaxCols = 32;       // largest batch; columns of a decode pass
 constexpr int kPassCols = 2048;    // most columns of a prompt chunk on the matrix-core path (a context holds min(this, max_seq rounded up to 128))
 constexpr int kMaxSplits = 32;     // context splits of one attention head
 constexpr size_t kGemmPartBytes = 16u << 20;   // partial accumulators of a K-sliced wide MFMA projection
+constexpr size_t kPromptPartBytes = 64u << 20; // ... and of a K-sliced residual projection of the prompt pass (at most 512 workgroups of 128 KB)
 constexpr int kGemmPartTickets = 2048;         // row groups such a projection may have
 constexpr int kSsqStride = 512;    // partial sums of squares kept per column (one per workgroup of the producing projection)
 
@@ -115,7 +116,7 @@ struct GemvArgs {
 // D3_MFMA_WIDE=0: no panel kernel (passes are limited to kMaxCols columns); D3_WIDE_RT, D3_WIDE_KS: row tiles per wave
 // and K slices of the panel kernel; D3_WIDE_SPLIT_MB: matrix size above which a pass of more than 64 columns runs as
 // two 64-column launches; D3_ATTN_MFMA=0: grouped-query and query-tile attention on the vector ALUs;
-// D3_ATTN_MIN_SPLIT: shortest context split; D3_PREFILL_COLS: columns per prompt chunk (a multiple of 64, at most 2048); D3_GEMV_WGS_PER_CU: workgroups
+// D3_ATTN_MIN_SPLIT: shortest context split; D3_PREFILL_COLS: columns per prompt chunk (a multiple of 64, at most 2048); D3_PROMPT_KS: K parts of a residual projection of the prompt pass (1..4); D3_GEMV_WGS_PER_CU: workgroups
 // per compute unit of the vector-ALU GEMV (default 3).
 struct Tuning {
     int gemv_wgs_per_cu = 3;
@@ -126,6 +127,7 @@ struct Tuning {
     bool attn_mfma = true;
     int attn_min_split = 128;
     int prefill_cols = 0;
+    int prompt_ks = 0;
 };
 Tuning tuning_from_env();
 
@@ -134,7 +136,7 @@ int launch_gemv_alu(const GemvArgs& a, int weight_dtype, int mode, bool norm, in
 // n_groups: workgroups launched (= parts written to ssq_out)
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups = nullptr);
 int launch_gemm_mfma_wide(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups);   // 17..128 columns
-int launch_gemm_prompt(const GemvArgs& a, int mode, hipStream_t s, int* n_groups);   // 129..kPassCols columns: LDS-tiled, compute-bound
+int launch_gemm_prompt(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups);   // 129..kPassCols columns: LDS-tiled, compute-bound
 size_t gemv_alu_max_cols(int K, int weight_dtype);   // columns one ALU launch can take (LDS bound)
 
 // first step of a pass on the MFMA path: hi + lo = x * gain (bf16 halves), ssq[col * kSsqStride] = sum(x^2)

@@ -279,7 +279,7 @@ int launch_mode(const GemvArgs& a, int mode, int rt, int tiles, int waves, size_
 int launch_gemm_mfma(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int nt = a.ncols > 16 ? 2 : 1;
-    if (a.ncols > 128 && a.part && tn.mfma_wide) return launch_gemm_prompt(a, mode, s, n_groups);
+    if (a.ncols > 128 && a.part && tn.mfma_wide) return launch_gemm_prompt(a, mode, n_cu, tn, s, n_groups);
     if (nt == 2 && a.part && tn.mfma_wide) return launch_gemm_mfma_wide(a, mode, n_cu, tn, s, n_groups);
     if (a.ncols > kMaxCols) return (int)hipErrorInvalidValue;
     const int sw = mode == MODE_SWIGLU ? 2 : 1;

@@ -21,6 +21,7 @@
 //  * gemm_prompt_w8_kernel (the residual projections, whose 256 tiles are one per compute unit): eight waves (4 x 2), 64 x
 //    64 per wave, four LDS buffers, and two sets of fragments in registers: while the MFMAs of stage t run from one set,
 //    the LDS reads of stage t + 1 fill the other.
+//    A long residual contraction is cut into K parts instead, one workgroup each on the four-wave kernel (see the launcher).
 // The LDS reads are inline assembly: the compiler orders every LDS read it knows of behind ALL outstanding direct-to-LDS
 // loads, which would drain the prefetch at every stage.  Here the vmcnt / lgkmcnt waits are written out (a wave's loads
 // complete in issue order, NL per stage), and empty asm statements that name the fragments as operands keep the MFMAs
@@ -203,14 +204,15 @@ struct PromptSetup {
     typedef PromptTile<RW, WY> Tile;
     static constexpr int SW = (MODE == MODE_SWIGLU) ? 2 : 1;
     static constexpr int OT = WY * RW / SW;            // output row tiles per workgroup (half as many gate/up pairs)
-    int rb, cb, tiles;
+    int rb, cb, tiles, slice;                          // slice: which of the ks parts of K this workgroup walks
     const bf16_t* src[Tile::NL];                       // this lane's piece of each of the wave's sixteen-row blocks, at k = 0
     uint32_t a_off, b_off;                             // LDS addresses of this lane's first weight / activation fragment in buffer 0
 
-    __device__ __forceinline__ bool init(const GemvArgs& a, int n_rb, int n_cb, int wave, int lane, float* inv_rms) {
+    __device__ __forceinline__ bool init(const GemvArgs& a, int n_rb, int n_cb, int ks, int wave, int lane, float* inv_rms) {
         const int per_group = 8 * n_cb;
-        rb = (blockIdx.x / per_group) * 8 + (blockIdx.x % per_group) % 8;
+        const int v = (blockIdx.x / per_group) * 8 + (blockIdx.x % per_group) % 8;   // row block x K part
         cb = (blockIdx.x % per_group) / 8;
+        rb = v / ks; slice = v - rb * ks;
         if (rb >= n_rb) return false;
         const int K = a.K;
         tiles = a.total_rows / 16;                     // output row tiles of the whole matrix
@@ -281,17 +283,19 @@ struct PromptSetup {
 // landed, nobody still reads stage t - 1), request stage t + 1 into the other buffer, read the 16 fragments, and
 // multiply column tile by column tile as its fragments arrive.
 template <int MODE>
-__global__ __launch_bounds__(256, 2) void gemm_prompt_w4_kernel(GemvArgs a, int n_rb, int n_cb) {
+__global__ __launch_bounds__(256, 2) void gemm_prompt_w4_kernel(GemvArgs a, int n_rb, int n_cb, int ks) {
     constexpr int RW = 8, WY = 2;
     typedef PromptTile<RW, WY> Tile;
     __shared__ float inv_rms[kTileN];
     __shared__ float ssq_w[WY][kTileN];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    __shared__ int is_last;
     PromptSetup<MODE, RW, WY> su;
-    if (!su.init(a, n_rb, n_cb, wave, lane, inv_rms)) return;
-    const int n_stages = a.K / kBK;
-    su.dma(0, 0, wave);
+    if (!su.init(a, n_rb, n_cb, ks, wave, lane, inv_rms)) return;
+    const int all_stages = a.K / kBK;
+    const int s0 = (int)((long long)all_stages * su.slice / ks), n_stages = (int)((long long)all_stages * (su.slice + 1) / ks) - s0;
+    su.dma(s0, 0, wave);
 
     f32x4 acc[RW][4];                                  // [slab tile of the wave][column tile of the wave]
 #pragma unroll
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void gemm_prompt_w4_kernel(GemvArgs a, int 
     for (int t = 0; t < n_stages; ++t) {
         vm_loads_left<0>();                            // this wave's part of stage t has landed ...
         __syncthreads();                               // ... and everybody's; nobody still reads stage t - 1 (and inv_rms is written)
-        if (t + 1 < n_stages) su.dma(t + 1, (t + 1) & 1, wave);
+        if (t + 1 < n_stages) su.dma(s0 + t + 1, (t + 1) & 1, wave);
         read_frags<RW>(f, su.a_off + (t & 1) * Tile::kStage, su.b_off + (t & 1) * Tile::kStage);
         lds_reads_left<6>();                           // the weight tiles and column tile 0
 #pragma unroll
@@ -324,6 +328,45 @@ __global__ __launch_bounds__(256, 2) void gemm_prompt_w4_kernel(GemvArgs a, int 
         __builtin_amdgcn_sched_barrier(0);
     }
     asm volatile("" ::: "memory");                     // the epilogue's loads stay behind the last stage
+    // ---- K parts: publish, count arrivals, the last one adds the parts up in order (independent of arrival order) ----
+    if (ks > 1) {
+        constexpr int ACC = RW * 4 * 4;
+        const int tile_id = su.rb * n_cb + su.cb;
+        float* mine = a.part + (((size_t)tile_id * ks + su.slice) * 4 + wave) * (ACC * 64) + lane;
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) st_agent(mine + ((r * 4 + tt) * 4 + e) * 64, acc[r][tt][e]);
+        wait_stores();                                 // this part's partials have reached the coherence point
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int* ticket = &a.part_tickets[tile_id];
+            const int done = atomicAdd(ticket, 1);
+            is_last = done == ks - 1;
+            if (is_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // all arrived: leave it clean
+        }
+        __syncthreads();
+        if (!is_last) return;
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int tt = 0; tt < 4; ++tt) acc[r][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int part = 0; part < ks; ++part) {
+            const float* p = a.part + (((size_t)tile_id * ks + part) * 4 + wave) * (ACC * 64) + lane;
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt) {
+                    float v[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = ld_agent(p + ((r * 4 + tt) * 4 + e) * 64);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[r][tt][e] += v[e];
+                }
+        }
+    }
     prompt_epilogue<MODE, RW, WY>(a, acc, su.rb, su.cb, su.tiles, inv_rms, ssq_w);
 }
 
@@ -345,7 +388,7 @@ __global__ __launch_bounds__(512, 2) void gemm_prompt_w8_kernel(GemvArgs a, int 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     PromptSetup<MODE, RW, WY> su;
-    if (!su.init(a, n_rb, n_cb, wave, lane, inv_rms)) return;
+    if (!su.init(a, n_rb, n_cb, 1, wave, lane, inv_rms)) return;
     const int n_stages = a.K / kBK;
     su.dma(0, 0, wave); su.dma(1, 1, wave); su.dma(2, 2, wave); su.dma(3, 3, wave);
 
@@ -446,29 +489,27 @@ __global__ __launch_bounds__(512, 2) void mfma_yardstick_kernel(float* __restric
     if (lane == 0) sink[blockIdx.x * 8 + wave] = sum;
 }
 
-template <typename Kern>
-int launch_prompt(Kern* k, int threads, int lds, const GemvArgs& a, int n_rb, int n_cb, hipStream_t s, hipError_t attr) {
-    if (attr != hipSuccess) return (int)attr;
-    hipLaunchKernelGGL(k, dim3((n_rb + 7) / 8 * 8 * n_cb), dim3(threads), lds, s, a, n_rb, n_cb);
-    return (int)hipGetLastError();
-}
 template <int MODE>
-int launch_w4(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
+int launch_w4(const GemvArgs& a, int n_rb, int n_cb, int ks, hipStream_t s) {
     constexpr int lds = 2 * PromptTile<8, 2>::kStage;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prompt_w4_kernel<MODE>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    return launch_prompt(gemm_prompt_w4_kernel<MODE>, 256, lds, a, n_rb, n_cb, s, attr);
+    if (attr != hipSuccess) return (int)attr;
+    hipLaunchKernelGGL(gemm_prompt_w4_kernel<MODE>, dim3((n_rb * ks + 7) / 8 * 8 * n_cb), dim3(256), lds, s, a, n_rb, n_cb, ks);
+    return (int)hipGetLastError();
 }
 int launch_w8_resid(const GemvArgs& a, int n_rb, int n_cb, hipStream_t s) {
     constexpr int lds = 4 * PromptTile<4, 4>::kStage;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_prompt_w8_kernel<MODE_RESID>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    return launch_prompt(gemm_prompt_w8_kernel<MODE_RESID>, 512, lds, a, n_rb, n_cb, s, attr);
+    if (attr != hipSuccess) return (int)attr;
+    hipLaunchKernelGGL(gemm_prompt_w8_kernel<MODE_RESID>, dim3((n_rb + 7) / 8 * 8 * n_cb), dim3(512), lds, s, a, n_rb, n_cb);
+    return (int)hipGetLastError();
 }
 
 }  // namespace
 
 // Requirements: those of launch_gemm_mfma (bf16 weights, K % 32 == 0, row counts multiples of 16), 1 <= ncols <=
 // kPassCols (x_hi / x_lo hold ncols rounded up to 128 rows); with ssq_out at most kSsqStride row blocks.
-int launch_gemm_prompt(const GemvArgs& a, int mode, hipStream_t s, int* n_groups) {
+int launch_gemm_prompt(const GemvArgs& a, int mode, int n_cu, const Tuning& tn, hipStream_t s, int* n_groups) {
     const int tiles = a.total_rows / 16;
     const int n_cb = (a.ncols + kTileN - 1) / kTileN;
     if (a.ncols < 1 || a.ncols > kPassCols || a.K % kBK != 0 || a.K < kBK) return (int)hipErrorInvalidValue;
@@ -477,10 +518,25 @@ int launch_gemm_prompt(const GemvArgs& a, int mode, hipStream_t s, int* n_groups
     if (a.ssq_out && n_rb > kSsqStride) return (int)hipErrorInvalidValue;
     if (n_groups) *n_groups = n_rb;
     const int n_stages = a.K / kBK;
-    if (mode == MODE_STORE) return launch_w4<MODE_STORE>(a, n_rb, n_cb, s);
-    if (mode == MODE_SWIGLU) return launch_w4<MODE_SWIGLU>(a, n_rb, n_cb, s);
+    if (mode == MODE_STORE) return launch_w4<MODE_STORE>(a, n_rb, n_cb, 1, s);
+    if (mode == MODE_SWIGLU) return launch_w4<MODE_SWIGLU>(a, n_rb, n_cb, 1, s);
+    // A residual projection has few tiles (4096 rows x 2048 columns: 256, one per compute unit).  With room for a second
+    // workgroup per compute unit K is cut into parts, one workgroup each on the four-wave kernel; the parts publish their
+    // accumulators (128 KB) and the one that arrives last at the tile's counter adds them up in part order.  That costs
+    // 40-65 us per launch (7B shape), so a part must keep enough stages: 96, or 48 when the tiles alone would leave a quarter
+    // of the compute units idle (7B shape, 2048 columns: down 395 -> 362 us in two parts, O 166 -> 185 and left whole; 13B
+    // shape, 1024 columns, 160 tiles: down 447 -> 314 in three parts, O 192 -> 173).
+    const int tiles_wg = n_rb * n_cb;
+    int ks = 2 * n_cu / tiles_wg;
+    if (ks > 4) ks = 4;
+    const int min_part = 4 * tiles_wg < 3 * n_cu ? 48 : 96;
+    while (ks > 1 && n_stages / ks < min_part) --ks;
+    if (tn.prompt_ks >= 1 && tn.prompt_ks <= n_stages) ks = tn.prompt_ks;
+    if (ks < 1) ks = 1;
+    if (ks > 1 && a.part && a.part_tickets && tiles_wg <= kGemmPartTickets && (size_t)tiles_wg * ks * 4 * 128 * 64 * sizeof(float) <= kPromptPartBytes)
+        return launch_w4<MODE_RESID>(a, n_rb, n_cb, ks, s);
     if (n_stages >= 4 && n_stages % 2 == 0) return launch_w8_resid(a, n_rb, n_cb, s);
-    return launch_w4<MODE_RESID>(a, n_rb, n_cb, s);
+    return launch_w4<MODE_RESID>(a, n_rb, n_cb, 1, s);
 }
 
 // mode 0: MFMAs alone; 1: with the fragment reads of the stage loop; 2: with the stage barrier as well.  n_wg workgroups of

@@ -130,6 +130,17 @@ def test_prompt_chunks_of_a_forced_width(monkeypatch, cols):
     _run(SMALL_GQA, 2, 150 if cols == 64 else 700, 4, 0.8, 1, forced_seed=9)
 
 
+@pytest.mark.parametrize("ks", [2, 3, 4])
+def test_prompt_residual_projections_in_k_parts(monkeypatch, ks):
+    # the residual projections of a prompt chunk with K cut into 2, 3 and 4 parts (one workgroup each; the part that arrives
+    # last at the tile's counter adds the published accumulators in part order): K of 16 and 43 stages (uneven parts),
+    # then 8 and 22 stages; by itself the launcher cuts K only for long contractions (the 7B / 13B / 70B widths, which
+    # the all-block and full-size tests run)
+    monkeypatch.setenv("D3_PROMPT_KS", str(ks))
+    _run(SMALL_GQA, 1, 300, 3, 0.8, 1, forced_seed=21)
+    _run(SMALL_BF16, 2, 200, 3, 0.9, 2, forced_seed=21)
+
+
 def test_lds_tiled_prompt_kernel_shapes():
     # rows that do not fill the last row block (d_ffn 1376 = 10.75 blocks of 128 gate/up pairs, vocab 2000), five and a half
     # column blocks; K of 16 stages (four-wave kernel) and 43 stages (odd: the residual projection cannot pair its stages

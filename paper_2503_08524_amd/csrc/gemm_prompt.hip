@@ -28,8 +28,9 @@
 // behind the waits.  7B shape, 2048 columns: QKV 432 -> 350 us, gate/up 805 -> 660, O 167 -> 158, down 402 -> 382
 // against the version that staged the slabs through registers (global -> VGPR -> ds_write, 64 x 64 per wave, fragments
 // read and multiplied in turns).  Measured with the operands' loads taken out, the stage loop of the eight-wave kernel
-// (LDS reads, MFMAs, barrier) takes 68 % of the full time; the matrix cores alone sustain 2.0 PFLOP/s on this chip
-// (80 % of the nominal peak: the clock drops under MFMA load), 1.8 with the LDS reads of this loop beside them.
+// (LDS reads, MFMAs, barrier) takes 68 % of the full time; the matrix cores alone sustain 2.06-2.23 PFLOP/s on this chip
+// (82-89 % of the nominal peak: the clock drops under MFMA load), 1.92-2.06 with the LDS reads of this loop beside them
+// (mfma_yardstick_kernel below).
 //
 // Workgroup order: the column blocks of one row block are 8 apart in the launch order, which puts them on one XCD at the
 // same time (workgroups go to the XCDs round-robin), so a weight slab pulled into that XCD's L2 serves all of them.  The
